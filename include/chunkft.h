@@ -1,0 +1,229 @@
+/*
+ * libchunkft -- the ChunkFT hot path on one MI355X (gfx950).
+ *
+ * ChunkFT fine-tunes all parameters of a model by rotating over "chunks":
+ * byte-budgeted, contiguous element ranges of the flattened row-major
+ * parameter tensors.  At each step only the active chunk gets a gradient
+ * (never a dense one) and an AdamW update whose fp32 master weights and
+ * moments exist for that chunk alone.  This library is that step:
+ *
+ *   chunkft_plan_cycle         byte budget -> chunks covering every element once
+ *   chunkft_chunk_wgrad        g[chunk] = (dY^T X)[chunk], dense dW never formed
+ *   chunkft_adamw_chunk        AdamW on the chunk's fp32 state (+ bf16 write-back)
+ *   chunkft_wgrad_adamw_fused  both, g never leaving the chip when it need not
+ *
+ * Conventions
+ *   - A linear layer computes y = x W^T; W is [out, in] row-major, X is
+ *     [T, in], dY is [T, out], T = batch x sequence flattened.
+ *   - A chunk segment on one tensor is the flat element range [begin, end),
+ *     flat = r * in + c.  It may start and end mid-row.
+ *   - Chunk-local arrays (g, master, m, v) hold element `begin + i` at index i.
+ *   - All sizes and offsets are in ELEMENTS unless the name ends in _bytes.
+ *   - Pointers marked (device) must be device memory reachable from the
+ *     current HIP device; pointers marked (host) are ordinary host memory.
+ *   - The library allocates no device memory and keeps no state between
+ *     calls.  Every buffer is owned by the caller.
+ *   - Device entry points validate their arguments synchronously, then
+ *     enqueue kernels on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and return without waiting.  They return CHUNKFT_OK or
+ *     a negative chunkft_status; nothing throws or aborts across this ABI,
+ *     and on an error status no kernel has been enqueued.
+ *   - Identical inputs give bit-identical outputs on every call.
+ */
+#ifndef CHUNKFT_H
+#define CHUNKFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CHUNKFT_OK = 0,
+  CHUNKFT_ERR_INVALID_ARG = -1,      /* null pointer, non-positive size, bad stride, bad hyper-parameter */
+  CHUNKFT_ERR_RANGE = -2,            /* [begin, end) empty or outside the tensor */
+  CHUNKFT_ERR_DTYPE = -3,            /* unknown dtype / kind, or a combination not supported */
+  CHUNKFT_ERR_WORKSPACE = -4,        /* workspace missing, misaligned or smaller than chunkft_workspace_bytes */
+  CHUNKFT_ERR_BUFFER_TOO_SMALL = -5, /* planner output arrays too short; required counts were written */
+  CHUNKFT_ERR_HIP = -6,              /* the HIP runtime refused a launch */
+  CHUNKFT_ERR_OVERFLOW = -7          /* an element or byte count does not fit int64 */
+} chunkft_status;
+
+typedef enum { CHUNKFT_F32 = 0, CHUNKFT_BF16 = 1 } chunkft_dtype;
+
+/* LINEAR: a weight matrix.  VECTOR: a 1-D scale vector (LayerNorm / RMSNorm
+ * weight), described as rows = 1, cols = length. */
+typedef enum { CHUNKFT_LINEAR = 0, CHUNKFT_VECTOR = 1 } chunkft_kind;
+
+/* ------------------------------------------------------------------------
+ * Cycle planner (host only)
+ *
+ * Paper: Section 3 "Method", first paragraph, and Algorithm 1 lines 1-2: the
+ * size of a tensor is numel x element_size; parameters are accumulated in
+ * model order until a byte budget is reached; a tensor larger than what is
+ * left is split and so spans several chunks.  The chunks are a disjoint
+ * partition of all trainable elements (Section 3.2).
+ * ---------------------------------------------------------------------- */
+typedef struct {
+  int64_t rows, cols;   /* W is rows x cols (out x in); VECTOR: rows = 1 */
+  int32_t dtype;        /* chunkft_dtype of the stored parameter */
+  int32_t kind;         /* chunkft_kind */
+} chunkft_tensor_desc;
+
+typedef struct {
+  int32_t tensor;       /* index into the tensor array */
+  int32_t reserved;     /* written as 0 */
+  int64_t begin, end;   /* flat element range of that tensor */
+  int64_t chunk_off;    /* index of `begin` in the chunk-local state arrays */
+} chunkft_segment;
+
+typedef struct {
+  int64_t seg_begin, seg_end; /* this chunk's segments are segs[seg_begin, seg_end) */
+  int64_t numel;              /* elements in the chunk = length of its g/master/m/v */
+  int64_t cost_bytes;         /* bytes charged against the budget */
+} chunkft_chunk;
+
+/* flags */
+#define CHUNKFT_PLAN_GREEDY 0u
+/* Charge each element its full training footprint instead of its storage size:
+ * parameter + fp32 gradient + fp32 master + fp32 m + fp32 v = element_size + 16
+ * (the cost listed in Section 3.1, first paragraph). */
+#define CHUNKFT_PLAN_TRAINING_COST 1u
+/* Keep the greedy chunk count K but lower the per-chunk budget to the
+ * smallest multiple of 4 bytes >= ceil(total / K) for which K chunks still
+ * suffice, so every chunk is close to the mean cost (byte-balance condition,
+ * Appendix "Analysis of Memory Jitter"). */
+#define CHUNKFT_PLAN_BALANCED 2u
+
+/*
+ * tensors (host, in)   n_tensors descriptors in model order.
+ * budget_bytes         > 0 and >= the per-element cost of every non-empty tensor.
+ * chunks (host, out)   array of chunks_cap entries, may be NULL when chunks_cap = 0.
+ * segs (host, out)     array of segs_cap entries, may be NULL when segs_cap = 0.
+ * n_chunks, n_segs (host, out, required)  always receive the counts the plan needs.
+ *
+ * Count-then-fill: if either capacity is short the counts are still written,
+ * the arrays are left untouched and CHUNKFT_ERR_BUFFER_TOO_SMALL is returned.
+ * Zero-element tensors produce no segment; an empty tensor list gives 0 chunks.
+ * Errors: CHUNKFT_ERR_INVALID_ARG (null required pointer, budget too small,
+ * negative shape, unknown flag), CHUNKFT_ERR_DTYPE, CHUNKFT_ERR_OVERFLOW.
+ */
+int chunkft_plan_cycle(const chunkft_tensor_desc* tensors, int32_t n_tensors,
+                       int64_t budget_bytes, uint32_t flags,
+                       chunkft_chunk* chunks, int64_t chunks_cap, int64_t* n_chunks,
+                       chunkft_segment* segs, int64_t segs_cap, int64_t* n_segs);
+
+/* ------------------------------------------------------------------------
+ * Layer operands of one backward step
+ * ---------------------------------------------------------------------- */
+typedef struct {
+  int32_t kind;      /* chunkft_kind */
+  int32_t dtype;     /* chunkft_dtype of X, dY (and of W in the fused call) */
+  int64_t out, in;   /* W shape; VECTOR: out = 1, in = vector length */
+  int64_t T;         /* tokens */
+  const void* X;     /* (device) LINEAR: [T, in] layer input.  VECTOR: [T, in] the
+                        normalised activations that the scale multiplies */
+  int64_t ldx;       /* row stride of X in elements, >= in */
+  const void* dY;    /* (device) LINEAR: [T, out] output gradient.  VECTOR: [T, in] */
+  int64_t lddy;      /* row stride of dY in elements */
+  int32_t split_k;   /* 0: the library picks the number of token slabs S from the
+                        shape alone; 1..64: use exactly this S */
+  int32_t reserved;  /* must be 0 */
+} chunkft_layer;
+
+/* Number of token slabs S the two wgrad entry points will use for this call
+ * (pure function of the layer shape, the range and split_k), or a negative
+ * status.  Host only. */
+int chunkft_split_k(const chunkft_layer* L, int64_t begin, int64_t end);
+
+/* Bytes of device workspace the two wgrad entry points need for this call:
+ * 0 when S = 1, else S * (end - begin) * 4 for the per-slab partial sums.
+ * Returns 0 also for invalid arguments (the call itself reports those). */
+size_t chunkft_workspace_bytes(const chunkft_layer* L, int64_t begin, int64_t end);
+
+/* ------------------------------------------------------------------------
+ * Chunk-restricted weight gradient
+ *
+ * Paper: Section 3.1, equation g^(k) = grad_{theta^(k)} L -- the backward pass
+ * produces the gradient of the active slices only, into an auxiliary fp32
+ * buffer, never a dense gradient (also Algorithm 1 line 18).  For y = x W^T:
+ *   LINEAR  g[i] = sum_t dY[t, r] * X[t, c],  begin + i = r * in + c
+ *   VECTOR  g[i] = sum_t dY[t, j] * X[t, j],  j = begin + i
+ * Products and sums are fp32 (bf16 inputs are multiplied exactly); the sum
+ * over tokens is taken slab by slab in a fixed order.
+ *
+ * g (device, out)   end - begin floats.  accumulate = 0: overwritten;
+ *                   accumulate = 1: g += result (gradient accumulation over
+ *                   micro-batches, Algorithm 1 line 14).
+ * ws (device)       workspace of at least chunkft_workspace_bytes(), 16-byte
+ *                   aligned; may be NULL when that is 0.  Contents on entry
+ *                   are ignored; on return they are unspecified.
+ * Only elements [0, end - begin) of g are written; nothing else is touched.
+ * Errors: INVALID_ARG, RANGE, DTYPE, WORKSPACE, HIP.
+ * ---------------------------------------------------------------------- */
+int chunkft_chunk_wgrad(const chunkft_layer* L, int64_t begin, int64_t end,
+                        float* g, int accumulate,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * AdamW on a chunk
+ *
+ * Paper: Algorithm 1 lines 19-21, element by element, in fp32:
+ *   m <- b1 m + (1 - b1) g          v <- b2 v + (1 - b2) g^2
+ *   mhat = m / (1 - b1^n)           vhat = v / (1 - b2^n)
+ *   theta <- theta - lr * ( mhat / (sqrt(vhat) + eps) + wd * theta )
+ * with theta on the right the value before the update and n the chunk's own
+ * update counter after its increment (Section 3.1: each chunk keeps a local
+ * counter for bias correction).  The library never counts: pass n as `step`.
+ * ---------------------------------------------------------------------- */
+typedef struct {
+  double lr, beta1, beta2, eps, weight_decay;
+  int64_t step;   /* n >= 1 */
+} chunkft_adamw_hparams;
+
+/*
+ * g (device, in)            n floats.
+ * master, m, v (device)     n floats each, updated in place.
+ * W_at_begin (device, out)  NULL, or the low-precision parameter copy ALREADY
+ *                           offset to the chunk's first element; receives
+ *                           round-to-nearest-even(master) as w_dtype (only
+ *                           CHUNKFT_BF16 makes sense; CHUNKFT_F32 copies).
+ * n                         elements, > 0.  No alignment is required of any
+ *                           pointer beyond that of its element type.
+ * Errors: INVALID_ARG (null pointer, n <= 0, step < 1, betas outside [0,1),
+ * negative lr/eps), DTYPE, HIP.
+ */
+int chunkft_adamw_chunk(const float* g, float* master, float* m, float* v,
+                        void* W_at_begin, int32_t w_dtype, int64_t n,
+                        const chunkft_adamw_hparams* hp, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Fused: chunk gradient straight into the AdamW update
+ *
+ * Same arithmetic as chunkft_chunk_wgrad (accumulate = 0) followed by
+ * chunkft_adamw_chunk on its result, bit for bit, but g is consumed from the
+ * accumulators (S = 1) or from the slab partials (S > 1) and never stored
+ * (the "temporary chunk gradients" of Algorithm 1 line 22 do not exist).
+ *
+ * W (device, out)   BASE of the low-precision tensor [out, in] (NOT offset);
+ *                   elements [begin, end) receive the rounded master.  May be
+ *                   NULL (fp32 training: the master is the parameter).  With
+ *                   dtype F32 a non-NULL W receives an fp32 copy.
+ * master, m, v      (device) chunk-local, end - begin floats each, in place.
+ * Elements of W outside [begin, end) are never written.
+ * Errors: as the two calls above.
+ * ---------------------------------------------------------------------- */
+int chunkft_wgrad_adamw_fused(const chunkft_layer* L, int64_t begin, int64_t end,
+                              void* W, float* master, float* m, float* v,
+                              const chunkft_adamw_hparams* hp,
+                              void* ws, size_t ws_bytes, void* stream);
+
+const char* chunkft_status_string(int status);
+int chunkft_version(void);   /* major * 10000 + minor * 100 + patch */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHUNKFT_H */
