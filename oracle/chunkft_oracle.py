@@ -111,7 +111,9 @@ def plan_cycle(tensors: Sequence[Tuple[int, int, int]], budget_bytes: int,
     budget into the open chunk, close the chunk when not even one element of
     the current tensor fits.  Balanced: keep the greedy chunk count K but
     shrink the budget to the smallest multiple of 4 bytes, not below
-    ceil(total/K), for which greedy still needs only K chunks.
+    ceil(total/K) and below the caller's budget, for which greedy still needs
+    only K chunks; if there is none the caller's budget stands (no chunk may
+    exceed the predefined budget).
     """
     if budget_bytes <= 0:
         raise ValueError("budget must be positive")
@@ -129,11 +131,12 @@ def plan_cycle(tensors: Sequence[Tuple[int, int, int]], budget_bytes: int,
         b = -(-total // k)          # ceil
         b = -(-b // 4) * 4          # round up to a multiple of 4 bytes
         b = max(b, max(s for n, s in zip(numels, costs) if n > 0))
-        while True:
+        while b < budget_bytes:
             cand = _greedy(numels, costs, b)
             if len(cand) <= k:
                 return cand
             b += 4
+        # no smaller budget keeps K chunks: the caller's budget is the cap
     return chunks
 
 

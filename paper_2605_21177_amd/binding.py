@@ -1,0 +1,221 @@
+"""ctypes binding of libchunkft: argument marshalling only.
+
+Function names match the C ABI in include/chunkft.h.  Tensors are torch
+tensors on the GPU (torch is used for device memory and streams only); every
+step of the path runs in the library's kernels.  There is no fallback: if the
+shared library is missing, loading raises.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libchunkft.so")
+
+OK = 0
+ERR_INVALID_ARG = -1
+ERR_RANGE = -2
+ERR_DTYPE = -3
+ERR_WORKSPACE = -4
+ERR_BUFFER_TOO_SMALL = -5
+ERR_HIP = -6
+ERR_OVERFLOW = -7
+
+F32 = 0
+BF16 = 1
+LINEAR = 0
+VECTOR = 1
+
+PLAN_GREEDY = 0
+PLAN_TRAINING_COST = 1
+PLAN_BALANCED = 2
+
+
+class TensorDesc(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("dtype", C.c_int32), ("kind", C.c_int32)]
+
+
+class Segment(C.Structure):
+    _fields_ = [("tensor", C.c_int32), ("reserved", C.c_int32), ("begin", C.c_int64),
+                ("end", C.c_int64), ("chunk_off", C.c_int64)]
+
+
+class Chunk(C.Structure):
+    _fields_ = [("seg_begin", C.c_int64), ("seg_end", C.c_int64), ("numel", C.c_int64),
+                ("cost_bytes", C.c_int64)]
+
+
+class AdamWHparams(C.Structure):
+    _fields_ = [("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
+                ("weight_decay", C.c_double), ("step", C.c_int64)]
+
+
+class Layer(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("dtype", C.c_int32), ("out", C.c_int64), ("n_in", C.c_int64),
+                ("T", C.c_int64), ("X", C.c_void_p), ("ldx", C.c_int64), ("dY", C.c_void_p),
+                ("lddy", C.c_int64), ("split_k", C.c_int32), ("reserved", C.c_int32)]
+
+
+class ChunkFTError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2605_21177_amd.build` "
+                "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        L.chunkft_plan_cycle.restype = C.c_int
+        L.chunkft_plan_cycle.argtypes = [C.POINTER(TensorDesc), C.c_int32, C.c_int64, C.c_uint32,
+                                         C.POINTER(Chunk), C.c_int64, C.POINTER(C.c_int64),
+                                         C.POINTER(Segment), C.c_int64, C.POINTER(C.c_int64)]
+        L.chunkft_split_k.restype = C.c_int
+        L.chunkft_split_k.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64]
+        L.chunkft_workspace_bytes.restype = C.c_size_t
+        L.chunkft_workspace_bytes.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64]
+        L.chunkft_chunk_wgrad.restype = C.c_int
+        L.chunkft_chunk_wgrad.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64, C.c_void_p, C.c_int,
+                                          C.c_void_p, C.c_size_t, C.c_void_p]
+        L.chunkft_adamw_chunk.restype = C.c_int
+        L.chunkft_adamw_chunk.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_int32, C.c_int64, C.POINTER(AdamWHparams), C.c_void_p]
+        L.chunkft_wgrad_adamw_fused.restype = C.c_int
+        L.chunkft_wgrad_adamw_fused.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64, C.c_void_p,
+                                                C.c_void_p, C.c_void_p, C.c_void_p,
+                                                C.POINTER(AdamWHparams), C.c_void_p, C.c_size_t,
+                                                C.c_void_p]
+        L.chunkft_status_string.restype = C.c_char_p
+        L.chunkft_status_string.argtypes = [C.c_int]
+        L.chunkft_version.restype = C.c_int
+        L.chunkft_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+EXPORTS = ("chunkft_plan_cycle", "chunkft_split_k", "chunkft_workspace_bytes", "chunkft_chunk_wgrad",
+           "chunkft_adamw_chunk", "chunkft_wgrad_adamw_fused", "chunkft_status_string",
+           "chunkft_version")
+
+
+def status_string(status: int) -> str:
+    return lib().chunkft_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return lib().chunkft_version()
+
+
+# ---------------------------------------------------------------- planner
+def chunkft_plan_cycle(tensors: Sequence[Tuple[int, int, int, int]], budget_bytes: int, flags: int = 0,
+                       check: bool = True):
+    """tensors: (rows, cols, dtype, kind).  Returns (status, chunks, segments) with
+    chunks = [(seg_begin, seg_end, numel, cost_bytes)] and
+    segments = [(tensor, begin, end, chunk_off)]."""
+    n = len(tensors)
+    arr = (TensorDesc * max(n, 1))()
+    for i, (r, c, d, k) in enumerate(tensors):
+        arr[i] = TensorDesc(r, c, d, k)
+    nc, ns = C.c_int64(0), C.c_int64(0)
+    st = lib().chunkft_plan_cycle(arr, n, budget_bytes, flags, None, 0, C.byref(nc), None, 0, C.byref(ns))
+    if st not in (OK, ERR_BUFFER_TOO_SMALL):
+        if check:
+            raise ChunkFTError(st, "chunkft_plan_cycle")
+        return st, [], []
+    chunks = (Chunk * max(nc.value, 1))()
+    segs = (Segment * max(ns.value, 1))()
+    st = lib().chunkft_plan_cycle(arr, n, budget_bytes, flags, chunks, nc.value, C.byref(nc), segs,
+                                  ns.value, C.byref(ns))
+    if st != OK:
+        if check:
+            raise ChunkFTError(st, "chunkft_plan_cycle")
+        return st, [], []
+    out_c = [(chunks[i].seg_begin, chunks[i].seg_end, chunks[i].numel, chunks[i].cost_bytes)
+             for i in range(nc.value)]
+    out_s = [(segs[i].tensor, segs[i].begin, segs[i].end, segs[i].chunk_off) for i in range(ns.value)]
+    return OK, out_c, out_s
+
+
+# ---------------------------------------------------------- device calls
+def _torch_dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def make_layer(kind: int, X, dY, out: int, n_in: int, split_k: int = 0) -> Layer:
+    """Describe a backward step from two row-major 2-D device tensors."""
+    if X.dim() != 2 or dY.dim() != 2 or X.stride(1) != 1 or dY.stride(1) != 1:
+        raise ValueError("X and dY must be 2-D with unit inner stride")
+    if not (X.is_cuda and dY.is_cuda):
+        raise ValueError("X and dY must live on the GPU")
+    d = _torch_dtype_code(X)
+    if _torch_dtype_code(dY) != d:
+        raise TypeError("X and dY must share a dtype")
+    return Layer(kind, d, out, n_in, X.shape[0], X.data_ptr(), X.stride(0), dY.data_ptr(), dY.stride(0),
+                 split_k, 0)
+
+
+def _stream_ptr(stream) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def chunkft_split_k(layer: Layer, begin: int, end: int) -> int:
+    return lib().chunkft_split_k(C.byref(layer), begin, end)
+
+
+def chunkft_workspace_bytes(layer: Layer, begin: int, end: int) -> int:
+    return lib().chunkft_workspace_bytes(C.byref(layer), begin, end)
+
+
+def chunkft_chunk_wgrad(layer: Layer, begin: int, end: int, g, accumulate: bool = False, ws=None,
+                        stream=None, check: bool = True) -> int:
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    st = lib().chunkft_chunk_wgrad(C.byref(layer), begin, end, _ptr(g), int(accumulate), _ptr(ws),
+                                   ws_bytes, _stream_ptr(stream))
+    if check and st != OK:
+        raise ChunkFTError(st, "chunkft_chunk_wgrad")
+    return st
+
+
+def hparams(lr, beta1, beta2, eps, weight_decay, step) -> AdamWHparams:
+    return AdamWHparams(lr, beta1, beta2, eps, weight_decay, step)
+
+
+def chunkft_adamw_chunk(g, master, m, v, W_at_begin, n: int, hp: AdamWHparams, w_dtype: int = BF16,
+                        stream=None, check: bool = True) -> int:
+    st = lib().chunkft_adamw_chunk(_ptr(g), _ptr(master), _ptr(m), _ptr(v), _ptr(W_at_begin), w_dtype,
+                                   n, C.byref(hp), _stream_ptr(stream))
+    if check and st != OK:
+        raise ChunkFTError(st, "chunkft_adamw_chunk")
+    return st
+
+
+def chunkft_wgrad_adamw_fused(layer: Layer, begin: int, end: int, W, master, m, v, hp: AdamWHparams,
+                              ws=None, stream=None, check: bool = True) -> int:
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    st = lib().chunkft_wgrad_adamw_fused(C.byref(layer), begin, end, _ptr(W), _ptr(master), _ptr(m),
+                                         _ptr(v), C.byref(hp), _ptr(ws), ws_bytes, _stream_ptr(stream))
+    if check and st != OK:
+        raise ChunkFTError(st, "chunkft_wgrad_adamw_fused")
+    return st

@@ -1,0 +1,74 @@
+// Internal interface between the C ABI (api.cpp) and the gfx950 kernels (kernels.hip).
+#ifndef CHUNKFT_INTERNAL_H
+#define CHUNKFT_INTERNAL_H
+
+#include <cstddef>
+#include <cstdint>
+
+namespace chunkft {
+
+// AdamW constants, rounded once from double on the host.
+struct AdamWConsts {
+  float beta1, one_minus_beta1;
+  float beta2, one_minus_beta2;
+  float inv_bias1;   // 1 / (1 - beta1^n)
+  float inv_bias2;   // 1 / (1 - beta2^n)
+  float lr, eps, weight_decay;
+};
+
+// What a gradient value is turned into.
+enum EmitMode : int {
+  EMIT_STORE = 0,    // g[i] = val
+  EMIT_ACCUM = 1,    // g[i] += val
+  EMIT_PARTIAL = 2,  // ws[slab * E + i] = val   (split over tokens)
+  EMIT_ADAMW = 3     // AdamW on master/m/v[i], low-precision copy at W[flat]
+};
+
+enum WKind : int { W_NONE = 0, W_BF16 = 1, W_F32 = 2 };
+
+struct Sinks {
+  float* g;          // EMIT_STORE / EMIT_ACCUM
+  float* ws;         // EMIT_PARTIAL: [S][E]
+  float* master;     // EMIT_ADAMW
+  float* m;
+  float* v;
+  void* W;           // tensor base, or nullptr
+  int32_t w_kind;    // WKind
+  AdamWConsts c;
+};
+
+constexpr int kMaxEdgeRows = 9;
+
+struct WgradProblem {
+  const void* X;
+  const void* dY;
+  int64_t ldx, lddy;
+  int64_t out, in, T;
+  int64_t begin, end;     // flat range, E = end - begin
+  int32_t S;              // token slabs
+  int64_t kslab;          // tokens per slab (multiple of the kernel's K tile)
+};
+
+// Shape of the token split for a call: S slabs of kslab tokens (last one short).
+struct Split {
+  int32_t S;
+  int64_t kslab;
+};
+
+bool mfma_path_ok(const WgradProblem& p);                 // alignment / shape rules of the MFMA kernel
+Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T, int64_t begin,
+                 int64_t end, int32_t forced, bool mfma);
+
+// All launchers return a hipError_t as int (0 = success).
+int launch_wgrad_bf16_mfma(const WgradProblem& p, int mode, const Sinks& s, void* stream);
+int launch_wgrad_simt(const WgradProblem& p, int dtype, int mode, const Sinks& s, void* stream);
+int launch_colsum(const WgradProblem& p, int dtype, int mode, const Sinks& s, void* stream);
+// g = sum over slabs (EMIT_STORE / EMIT_ACCUM) or AdamW on that sum (EMIT_ADAMW).
+// W_at_begin is already offset to the first element.
+int launch_reduce(const float* ws, int32_t S, int64_t E, int mode, const Sinks& s, void* W_at_begin,
+                  void* stream);
+// AdamW with the gradient read from g.
+int launch_adamw(const float* g, int64_t n, const Sinks& s, void* W_at_begin, void* stream);
+
+}  // namespace chunkft
+#endif

@@ -1,0 +1,137 @@
+// Cycle planner: byte budget -> ordered chunks of tensor segments (host only).
+//
+// Follows the paper's Section 3 "Method" (first paragraph) and Algorithm 1
+// lines 1-2: every tensor costs numel x bytes-per-element, tensors are taken
+// in model order, a chunk is filled until the budget cannot take one more
+// element, and a tensor that does not fit is cut at that element, so it spans
+// chunks.  The optional training cost per element is the one of Section 3.1
+// (parameter + gradient + fp32 master + two moments).  Integer arithmetic only.
+
+#include "chunkft.h"
+
+#include <cstdint>
+#include <limits>
+#include <vector>
+
+namespace {
+
+constexpr int64_t kStateBytes = 16;  // fp32 gradient + master + m + v
+
+struct Costed {
+  int64_t numel;
+  int64_t cost;  // bytes charged per element
+};
+
+// One greedy pass.  With out == nullptr it only counts.
+struct Pass {
+  int64_t n_chunks = 0;
+  int64_t n_segs = 0;
+};
+
+Pass greedy(const std::vector<Costed>& ts, int64_t budget, chunkft_chunk* chunks,
+            chunkft_segment* segs) {
+  Pass p;
+  int64_t room = budget;
+  int64_t filled = 0;        // elements in the open chunk
+  int64_t seg_first = 0;     // first segment of the open chunk
+  auto close_chunk = [&]() {
+    if (chunks) {
+      chunkft_chunk& c = chunks[p.n_chunks];
+      c.seg_begin = seg_first;
+      c.seg_end = p.n_segs;
+      c.numel = filled;
+      c.cost_bytes = budget - room;
+    }
+    ++p.n_chunks;
+    room = budget;
+    filled = 0;
+    seg_first = p.n_segs;
+  };
+  for (size_t t = 0; t < ts.size(); ++t) {
+    int64_t pos = 0;
+    const int64_t n = ts[t].numel, s = ts[t].cost;
+    while (pos < n) {
+      int64_t take = room / s;
+      if (take > n - pos) take = n - pos;
+      if (take == 0) {       // not one more element of this tensor fits
+        close_chunk();
+        continue;
+      }
+      if (segs) {
+        chunkft_segment& g = segs[p.n_segs];
+        g.tensor = static_cast<int32_t>(t);
+        g.reserved = 0;
+        g.begin = pos;
+        g.end = pos + take;
+        g.chunk_off = filled;
+      }
+      ++p.n_segs;
+      pos += take;
+      filled += take;
+      room -= take * s;
+    }
+  }
+  if (filled > 0) close_chunk();
+  return p;
+}
+
+}  // namespace
+
+extern "C" int chunkft_plan_cycle(const chunkft_tensor_desc* tensors, int32_t n_tensors,
+                                  int64_t budget_bytes, uint32_t flags, chunkft_chunk* chunks,
+                                  int64_t chunks_cap, int64_t* n_chunks, chunkft_segment* segs,
+                                  int64_t segs_cap, int64_t* n_segs) {
+  if (!n_chunks || !n_segs) return CHUNKFT_ERR_INVALID_ARG;
+  *n_chunks = 0;
+  *n_segs = 0;
+  if (n_tensors < 0 || (n_tensors > 0 && !tensors)) return CHUNKFT_ERR_INVALID_ARG;
+  if (budget_bytes <= 0) return CHUNKFT_ERR_INVALID_ARG;
+  if (flags & ~(CHUNKFT_PLAN_TRAINING_COST | CHUNKFT_PLAN_BALANCED)) return CHUNKFT_ERR_INVALID_ARG;
+  if (chunks_cap < 0 || segs_cap < 0) return CHUNKFT_ERR_INVALID_ARG;
+  if ((chunks_cap > 0 && !chunks) || (segs_cap > 0 && !segs)) return CHUNKFT_ERR_INVALID_ARG;
+
+  const int64_t kMax = std::numeric_limits<int64_t>::max();
+  std::vector<Costed> ts(static_cast<size_t>(n_tensors));
+  int64_t total = 0, max_cost = 0;
+  for (int32_t t = 0; t < n_tensors; ++t) {
+    const chunkft_tensor_desc& d = tensors[t];
+    if (d.rows < 0 || d.cols < 0) return CHUNKFT_ERR_INVALID_ARG;
+    if (d.kind != CHUNKFT_LINEAR && d.kind != CHUNKFT_VECTOR) return CHUNKFT_ERR_DTYPE;
+    int64_t s;
+    if (d.dtype == CHUNKFT_F32) s = 4;
+    else if (d.dtype == CHUNKFT_BF16) s = 2;
+    else return CHUNKFT_ERR_DTYPE;
+    if (flags & CHUNKFT_PLAN_TRAINING_COST) s += kStateBytes;
+    if (d.rows != 0 && d.cols > kMax / d.rows) return CHUNKFT_ERR_OVERFLOW;
+    const int64_t n = d.rows * d.cols;
+    if (n != 0 && s > kMax / n) return CHUNKFT_ERR_OVERFLOW;
+    if (n * s > kMax - total) return CHUNKFT_ERR_OVERFLOW;
+    total += n * s;
+    if (n > 0) {
+      if (s > budget_bytes) return CHUNKFT_ERR_INVALID_ARG;
+      if (s > max_cost) max_cost = s;
+    }
+    ts[static_cast<size_t>(t)] = {n, s};
+  }
+
+  int64_t budget = budget_bytes;
+  Pass need = greedy(ts, budget, nullptr, nullptr);
+  if ((flags & CHUNKFT_PLAN_BALANCED) && need.n_chunks > 1) {
+    const int64_t k = need.n_chunks;
+    int64_t b = total / k + (total % k ? 1 : 0);
+    b = (b + 3) / 4 * 4;
+    if (b < max_cost) b = max_cost;
+    // b <= budget_bytes always terminates the search: greedy(budget_bytes) needs k chunks
+    for (;; b += 4) {
+      if (b >= budget_bytes) { b = budget_bytes; break; }
+      if (greedy(ts, b, nullptr, nullptr).n_chunks <= k) break;
+    }
+    budget = b;
+    need = greedy(ts, budget, nullptr, nullptr);
+  }
+  *n_chunks = need.n_chunks;
+  *n_segs = need.n_segs;
+  if (need.n_chunks > chunks_cap || need.n_segs > segs_cap) return CHUNKFT_ERR_BUFFER_TOO_SMALL;
+  greedy(ts, budget, chunks, segs);
+  return CHUNKFT_OK;
+}

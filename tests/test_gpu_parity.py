@@ -1,0 +1,264 @@
+"""GPU parity: libchunkft (through its C ABI) against the CPU oracle, element by
+element on the same seeded inputs.  Sizes here are ones the oracle finishes in
+seconds while still spanning several tiles, ragged tails and both code paths
+(MFMA body + FMA edge rows, FMA fallback, split over tokens)."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import chunkft_oracle as O
+from paper_2605_21177_amd import binding as B
+from paper_2605_21177_amd import workloads as WL
+
+import gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+HP = WL.HPARAMS
+TOL_G = {WL.BF16: 3e-3, WL.F32: 1e-5}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    H.require_gpu()
+
+
+def _state_for(case, begin, end, rng, warm):
+    th0 = WL.as_f64(case.W0).reshape(-1)[begin:end].astype(np.float32)
+    n = end - begin
+    if warm:
+        m0 = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+        v0 = (rng.standard_normal(n) ** 2 * 1e-6).astype(np.float32)
+    else:
+        m0 = np.zeros(n, np.float32)
+        v0 = np.zeros(n, np.float32)
+    return th0, m0, v0
+
+
+def _full_check(case, begin, end, split_k=None, warm=False, step=1, check_accum=True):
+    """wgrad, accumulate, fused (+ fused == un-fused + AdamW bit for bit), W untouched outside."""
+    dl = H.DeviceLayer(case)
+    X64, dY64 = WL.as_f64(case.X), WL.as_f64(case.dY)
+    if case.kind == WL.LINEAR:
+        g_ref = O.chunk_wgrad(X64, dY64, begin, end, dense=(case.numel <= (1 << 22)))
+    else:
+        g_ref = O.vector_wgrad(X64, dY64, begin, end)
+    n = end - begin
+
+    g = H.gpu_wgrad(dl, begin, end, split_k)
+    err = H.rel_frobenius(g, g_ref)
+    assert err <= TOL_G[case.dtype], f"gradient relative Frobenius error {err:.3e}"
+    # determinism: the same call again gives the same bits
+    g2 = H.gpu_wgrad(dl, begin, end, split_k)
+    assert np.array_equal(g, g2)
+
+    if check_accum:
+        rng = np.random.default_rng(5)
+        base = rng.standard_normal(n).astype(np.float32)
+        ga = H.gpu_wgrad(dl, begin, end, split_k, accumulate_into=torch.from_numpy(base))
+        assert np.array_equal(ga.astype(np.float32), (base + g.astype(np.float32)))
+
+    rng = np.random.default_rng(6)
+    th0, m0, v0 = _state_for(case, begin, end, rng, warm)
+    is_bf16 = case.dtype == WL.BF16
+    W0 = case.W0.reshape(-1) if is_bf16 else None
+    Wd, master, m, v = H.gpu_fused(dl, begin, end, W0, th0, m0, v0, HP, step, split_k)
+    W_bits = None
+    if is_bf16:
+        allbits = WL.bits_u16(Wd)
+        before = WL.bits_u16(case.W0.reshape(-1))
+        assert np.array_equal(allbits[:begin], before[:begin]) and np.array_equal(allbits[end:], before[end:]), \
+            "low-precision parameters outside the chunk changed"
+        W_bits = allbits[begin:end]
+    H.check_fused_against_oracle(g_ref, th0, m0, v0, HP, step, master, m, v, W_bits)
+
+    # the fused call equals the un-fused pair bit for bit
+    gdev = torch.from_numpy(g.astype(np.float32)).to(H.DEV)
+    Wslice = None
+    if is_bf16:
+        Wfull = case.W0.reshape(-1).clone().to(H.DEV)
+        Wslice = Wfull[begin:end]
+    master2, m2, v2 = H.gpu_adamw(gdev, th0, m0, v0, Wslice, HP, step)
+    assert np.array_equal(master, master2) and np.array_equal(m, m2) and np.array_equal(v, v2)
+    if is_bf16:
+        assert np.array_equal(WL.bits_u16(Wfull.cpu()), allbits)
+    return g, g_ref
+
+
+# ------------------------------------------------------------ configuration 1
+def test_config1_fp32_layer():
+    case, begin, end = WL.config1()
+    _full_check(case, begin, end)
+
+
+def test_config1_standalone_adamw_elementwise():
+    """The AdamW entry point alone, both sides fed the same fp32 gradient."""
+    case, begin, end = WL.config1()
+    g64 = O.chunk_wgrad(WL.as_f64(case.X), WL.as_f64(case.dY), begin, end)
+    g32 = g64.astype(np.float32)
+    th0 = WL.as_f64(case.W0).reshape(-1)[begin:end].astype(np.float32)
+    z = np.zeros_like(th0)
+    th, m, v = th0, z, z
+    gdev = torch.from_numpy(g32).to(H.DEV)
+    for step in (1, 2, 3):
+        ref = O.adamw_step(g32, th, m, v, step=step, **HP)
+        th, m, v = H.gpu_adamw(gdev, th, m, v, None, HP, step, w_dtype=B.F32)
+        H.assert_elementwise(th, ref[0], 1e-2, f"theta step {step}")
+        H.assert_elementwise(m, ref[1], 1e-2, f"m step {step}")
+        H.assert_elementwise(v, ref[2], 0.0, f"v step {step}")
+
+
+# -------------------------------------------------- adversarial ranges, bf16
+def _small_bf16(out=520, n_in=264, T=100, seed=77, sigma_dy=1e-3):
+    rng = np.random.default_rng(seed)
+    return WL.linear_case(rng, "small", out, n_in, T, WL.BF16, sigma_dy)
+
+
+RANGES_520x264 = [
+    (0, 520 * 264),                 # the whole tensor
+    (264 * 7 + 5, 264 * 7 + 6),     # a single element
+    (264 * 9 + 10, 264 * 9 + 200),  # inside one row
+    (264 * 16, 264 * 17),           # exactly one row, 8-aligned row index
+    (264 * 3, 264 * 4),             # exactly one row, unaligned row index
+    (264 * 8, 264 * 300 + 100),     # begin on a row boundary, end mid-row
+    (264 * 5 + 77, 264 * 400),      # begin mid-row, end on a row boundary
+    (264 * 2 + 33, 264 * 519 + 1),  # odd begin: 2-byte-aligned bf16 stores
+    (264 * 6 + 1, 264 * 9 + 263),   # few rows: one body row between edge rows
+    (264 * 1 + 1, 264 * 6 + 5),     # six rows, none of them in the 8-aligned body
+    (264 * 259 + 263, 264 * 519),   # starts on the last element of a row
+]
+
+
+@pytest.mark.parametrize("begin,end", RANGES_520x264)
+def test_bf16_ranges(begin, end):
+    _full_check(_small_bf16(), begin, end)
+
+
+@pytest.mark.parametrize("split_k", [2, 3, 4])
+def test_bf16_forced_token_split(split_k):
+    case = _small_bf16(T=200)
+    begin, end = 264 * 2 + 33, 264 * 519 + 1
+    g, _ = _full_check(case, begin, end, split_k=split_k, warm=True, step=2)
+    layer = H.DeviceLayer(case).layer(split_k)
+    assert B.chunkft_split_k(layer, begin, end) == split_k
+
+
+def test_bf16_unaligned_shape_takes_fma_path():
+    rng = np.random.default_rng(78)
+    case = WL.linear_case(rng, "odd", 137, 100, 53, WL.BF16, 1e-3)   # in, out not multiples of 8
+    for begin, end in ((0, 13700), (101, 9999), (5, 6)):
+        _full_check(case, begin, end)
+    _full_check(case, 101, 9999, split_k=2)
+
+
+def test_bf16_strided_operands():
+    """Row strides larger than the row length (views into wider buffers)."""
+    rng = np.random.default_rng(79)
+    out, n_in, T = 264, 136, 70
+    case = WL.linear_case(rng, "strided", out, n_in, T, WL.BF16, 1e-3)
+    Xw = torch.zeros(T, n_in + 24, dtype=torch.bfloat16, device=H.DEV)
+    dYw = torch.zeros(T, out + 40, dtype=torch.bfloat16, device=H.DEV)
+    Xw[:, :n_in] = case.X.to(H.DEV)
+    dYw[:, :out] = case.dY.to(H.DEV)
+    Xw[:, n_in:] = 99.0
+    dYw[:, out:] = 99.0             # must never be read into a result
+    layer = B.make_layer(B.LINEAR, Xw[:, :n_in], dYw[:, :out], out, n_in)
+    begin, end = 136 * 3 + 7, 136 * 260 + 3
+    full, g = H.guarded(end - begin)
+    B.chunkft_chunk_wgrad(layer, begin, end, g)
+    torch.cuda.synchronize()
+    g_ref = O.chunk_wgrad(WL.as_f64(case.X), WL.as_f64(case.dY), begin, end)
+    assert H.rel_frobenius(g.cpu().numpy(), g_ref) <= 3e-3 and H.guards_intact(full)
+
+
+def test_vector_kind():
+    rng = np.random.default_rng(80)
+    for dtype in (WL.BF16, WL.F32):
+        case = WL.vector_case(rng, "norm", 1000, 77, dtype, 1e-3)
+        for begin, end in ((0, 1000), (3, 997), (500, 501)):
+            _full_check(case, begin, end)
+
+
+def test_warm_state_second_step():
+    _full_check(_small_bf16(seed=81), 264 * 2 + 33, 264 * 519 + 1, warm=True, step=2)
+
+
+# ------------------------------------------- scaled-down configurations 2-5
+def test_config2_scaled():
+    case, begin, end = WL.config2(scale=4)          # 3584 x 1024, 2 Mi-element chunk
+    _full_check(case, begin, end)
+
+
+def test_config4_scaled_token_splits():
+    layers = WL.config4(scale=16, T=512)            # 1792 x 512 and 512 x 1792
+    rng = WL.rng_for(4, 2)
+    for case in layers:
+        length = case.numel // 3
+        begin = WL.draw_offset(rng, case.numel, length, case.n_in)
+        ref = None
+        for s in (1, 2, 4, 8):
+            g, g_ref = _full_check(case, begin, begin + length, split_k=s, check_accum=(s == 2))
+            ref = g_ref
+
+
+def test_config5_scaled_chunk_sizes():
+    case = WL.config5(scale=8, T=512)               # 16032 x 512
+    for begin, end in WL.config5_ranges(case, scale=8):
+        _full_check(case, begin, end, check_accum=False)
+
+
+def _run_cycle(layers, budget, flags=0):
+    """One full-parameter cycle on the GPU: plan, then one fused call per segment."""
+    tensors = [(c.out, c.n_in, c.dtype, c.kind) for c in layers]
+    st, chunks, segs = B.chunkft_plan_cycle(tensors, budget, flags)
+    dls = [H.DeviceLayer(c) for c in layers]
+    Wd = [c.W0.reshape(-1).clone().to(H.DEV) for c in layers]
+    masters, ms, vs = [], [], []
+    for (s0, s1, numel, _) in chunks:
+        master = torch.empty(numel, dtype=torch.float32, device=H.DEV)
+        for (t, b, e, off) in segs[s0:s1]:
+            master[off:off + (e - b)] = Wd[t][b:e].float()
+        m = torch.zeros(numel, dtype=torch.float32, device=H.DEV)
+        v = torch.zeros(numel, dtype=torch.float32, device=H.DEV)
+        for (t, b, e, off) in segs[s0:s1]:
+            layer = dls[t].layer()
+            ws = H.workspace_for(layer, b, e)
+            n = e - b
+            B.chunkft_wgrad_adamw_fused(layer, b, e, Wd[t], master[off:off + n], m[off:off + n],
+                                        v[off:off + n], B.hparams(step=1, **HP), ws=ws)
+        masters.append(master); ms.append(m); vs.append(v)
+    torch.cuda.synchronize()
+    return chunks, segs, Wd, masters, ms, vs
+
+
+@pytest.mark.parametrize("budget_mib_x16", [256, 64, 100])
+def test_config3_scaled_cycle(budget_mib_x16):
+    """The transformer block at 1/4 linear scale (1/16 of the elements), budgets
+    scaled alike (+2 bytes on the 100 MiB one to force mid-row cuts)."""
+    layers = WL.config3(scale=4, T=256)
+    budget = budget_mib_x16 * (1 << 20) // 16 + (2 if budget_mib_x16 == 100 else 0)
+    chunks, segs, Wd, masters, ms, vs = _run_cycle(layers, budget)
+    # the library's plan is the oracle's plan
+    oc = O.plan_cycle([c.desc() for c in layers], budget)
+    assert [(s.tensor, s.begin, s.end, s.chunk_off) for ch in oc for s in ch] == segs
+    # every element updated exactly once: compare with one dense AdamW step per tensor
+    for t, case in enumerate(layers):
+        X64, dY64 = WL.as_f64(case.X), WL.as_f64(case.dY)
+        g_ref = (O.dense_wgrad(X64, dY64).reshape(-1) if case.kind == WL.LINEAR
+                 else O.vector_wgrad(X64, dY64, 0, case.n_in))
+        th0 = WL.as_f64(case.W0).reshape(-1)
+        z = np.zeros_like(th0)
+        got_master = np.empty(case.numel, np.float32)
+        got_m = np.empty(case.numel, np.float32)
+        got_v = np.empty(case.numel, np.float32)
+        for k, (s0, s1, _, _) in enumerate(chunks):
+            for (tt, b, e, off) in segs[s0:s1]:
+                if tt == t:
+                    got_master[b:e] = masters[k][off:off + e - b].cpu().numpy()
+                    got_m[b:e] = ms[k][off:off + e - b].cpu().numpy()
+                    got_v[b:e] = vs[k][off:off + e - b].cpu().numpy()
+        bits = WL.bits_u16(Wd[t].cpu())
+        H.check_fused_against_oracle(g_ref, th0, z, z, HP, 1, got_master, got_m, got_v, bits)
+        # with a non-zero gradient every master value moved (update counter = 1 everywhere)
+        assert np.all(got_master != th0.astype(np.float32))

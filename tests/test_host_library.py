@@ -1,0 +1,200 @@
+"""Host-side checks of libchunkft (no GPU): exported symbols, the planner
+bit for bit against the oracle's planner, and argument validation (every call
+made here is rejected before anything could reach a device)."""
+
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import chunkft_oracle as O
+from paper_2605_21177_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "chunkft.h")).read()
+    declared = set(re.findall(r"\b(chunkft_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    lib = B.lib()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert B.version() >= 100
+    assert B.status_string(0) == "ok"
+    assert "workspace" in B.status_string(B.ERR_WORKSPACE)
+
+
+def _oracle_plan(tensors, budget, flags):
+    chunks = O.plan_cycle([(r, c, d) for r, c, d, _ in tensors], budget,
+                          training_cost=bool(flags & B.PLAN_TRAINING_COST),
+                          balanced=bool(flags & B.PLAN_BALANCED))
+    segs, cks = [], []
+    for ch in chunks:
+        s0 = len(segs)
+        segs += [(s.tensor, s.begin, s.end, s.chunk_off) for s in ch]
+        numel = sum(s.end - s.begin for s in ch)
+        cost = O.chunk_cost_bytes(ch, [(r, c, d) for r, c, d, _ in tensors],
+                                  bool(flags & B.PLAN_TRAINING_COST))
+        cks.append((s0, len(segs), numel, cost))
+    return cks, segs
+
+
+def test_planner_matches_oracle_block_configs():
+    h, kv, ff = 4096, 1024, 14336
+    tensors = [(h, h, 1, 0), (kv, h, 1, 0), (kv, h, 1, 0), (h, h, 1, 0), (ff, h, 1, 0), (ff, h, 1, 0),
+               (h, ff, 1, 0), (1, h, 1, 1), (1, h, 1, 1)]
+    for budget in (256 << 20, 64 << 20, (100 << 20) + 2, 1 << 20, 12345678):
+        for flags in (0, 1, 2, 3):
+            if flags & 1:
+                budget_f = budget * 9
+            else:
+                budget_f = budget
+            st, ck, sg = B.chunkft_plan_cycle(tensors, budget_f, flags)
+            assert st == B.OK
+            want_ck, want_sg = _oracle_plan(tensors, budget_f, flags)
+            assert sg == want_sg
+            assert ck == want_ck
+
+
+def test_planner_matches_oracle_random():
+    rng = np.random.default_rng(99)
+    for _ in range(300):
+        n = int(rng.integers(0, 8))
+        tensors = [(int(rng.integers(0, 40)), int(rng.integers(0, 40)), int(rng.integers(0, 2)),
+                    int(rng.integers(0, 2))) for _ in range(n)]
+        flags = int(rng.integers(0, 4))
+        budget = int(rng.integers(20 if flags & 1 else 4, 4000))
+        st, ck, sg = B.chunkft_plan_cycle(tensors, budget, flags)
+        assert st == B.OK
+        want_ck, want_sg = _oracle_plan(tensors, budget, flags)
+        assert (ck, sg) == (want_ck, want_sg)
+
+
+def test_planner_count_then_fill_and_errors():
+    lib = B.lib()
+    arr = (B.TensorDesc * 2)(B.TensorDesc(10, 10, 1, 0), B.TensorDesc(1, 7, 0, 1))
+    nc, ns = C.c_int64(-1), C.c_int64(-1)
+    # size query
+    st = lib.chunkft_plan_cycle(arr, 2, 64, 0, None, 0, C.byref(nc), None, 0, C.byref(ns))
+    assert st == B.ERR_BUFFER_TOO_SMALL
+    want = O.plan_cycle([(10, 10, 1), (1, 7, 0)], 64)
+    assert nc.value == len(want) and ns.value == sum(len(c) for c in want)
+    # short arrays are left untouched
+    chunks = (B.Chunk * 1)()
+    chunks[0].numel = -77
+    segs = (B.Segment * 1)()
+    st = lib.chunkft_plan_cycle(arr, 2, 64, 0, chunks, 1, C.byref(nc), segs, 1, C.byref(ns))
+    assert st == B.ERR_BUFFER_TOO_SMALL and chunks[0].numel == -77
+    # errors
+    assert lib.chunkft_plan_cycle(arr, 2, 64, 0, None, 0, None, None, 0, C.byref(ns)) == B.ERR_INVALID_ARG
+    assert lib.chunkft_plan_cycle(arr, 2, 0, 0, None, 0, C.byref(nc), None, 0, C.byref(ns)) == B.ERR_INVALID_ARG
+    assert lib.chunkft_plan_cycle(arr, 2, 3, 0, None, 0, C.byref(nc), None, 0, C.byref(ns)) == B.ERR_INVALID_ARG  # < 4 B fp32
+    assert lib.chunkft_plan_cycle(arr, 2, 64, 8, None, 0, C.byref(nc), None, 0, C.byref(ns)) == B.ERR_INVALID_ARG  # unknown flag
+    assert lib.chunkft_plan_cycle(None, 2, 64, 0, None, 0, C.byref(nc), None, 0, C.byref(ns)) == B.ERR_INVALID_ARG
+    bad = (B.TensorDesc * 1)(B.TensorDesc(10, 10, 5, 0))
+    assert lib.chunkft_plan_cycle(bad, 1, 64, 0, None, 0, C.byref(nc), None, 0, C.byref(ns)) == B.ERR_DTYPE
+    neg = (B.TensorDesc * 1)(B.TensorDesc(-1, 10, 1, 0))
+    assert lib.chunkft_plan_cycle(neg, 1, 64, 0, None, 0, C.byref(nc), None, 0, C.byref(ns)) == B.ERR_INVALID_ARG
+    big = (B.TensorDesc * 1)(B.TensorDesc(1 << 40, 1 << 40, 1, 0))
+    assert lib.chunkft_plan_cycle(big, 1, 64, 0, None, 0, C.byref(nc), None, 0, C.byref(ns)) == B.ERR_OVERFLOW
+    # empty list and zero-sized tensors
+    assert lib.chunkft_plan_cycle(None, 0, 64, 0, None, 0, C.byref(nc), None, 0, C.byref(ns)) == B.OK
+    assert nc.value == 0 and ns.value == 0
+    st, ck, sg = B.chunkft_plan_cycle([(0, 5, 1, 0), (3, 0, 0, 0)], 64)
+    assert (st, ck, sg) == (B.OK, [], [])
+
+
+def test_planner_large_counts_near_int64():
+    # 2^31 x 2^31 bf16 = 2^63 bytes does not fit; 2^30 x 2^31 does (2^62 bytes)
+    st, ck, sg = B.chunkft_plan_cycle([(1 << 30, 1 << 31, 1, 0)], 1 << 61)
+    assert st == B.OK and len(ck) == 2 and ck[0][2] == 1 << 60
+    st, _, _ = B.chunkft_plan_cycle([(1 << 31, 1 << 31, 1, 0)], 1 << 61, check=False)
+    assert st == B.ERR_OVERFLOW
+
+
+# fake non-null addresses: every call below must be rejected by validation
+P = 0x1000
+
+
+def _layer(**kw):
+    d = dict(kind=B.LINEAR, dtype=B.BF16, out=64, n_in=32, T=16, X=P, ldx=32, dY=P, lddy=64, split_k=0,
+             reserved=0)
+    d.update(kw)
+    return B.Layer(**d)
+
+
+def test_device_calls_reject_bad_arguments_without_launching():
+    lib = B.lib()
+    hp = B.hparams(1e-4, 0.9, 0.999, 1e-8, 0.01, 1)
+    cases = [
+        (_layer(X=None), 0, 10, B.ERR_INVALID_ARG),
+        (_layer(T=0), 0, 10, B.ERR_INVALID_ARG),
+        (_layer(ldx=31), 0, 10, B.ERR_INVALID_ARG),
+        (_layer(lddy=63), 0, 10, B.ERR_INVALID_ARG),
+        (_layer(dtype=7), 0, 10, B.ERR_DTYPE),
+        (_layer(kind=2), 0, 10, B.ERR_DTYPE),
+        (_layer(split_k=65), 0, 10, B.ERR_INVALID_ARG),
+        (_layer(reserved=1), 0, 10, B.ERR_INVALID_ARG),
+        (_layer(kind=B.VECTOR, out=2), 0, 10, B.ERR_INVALID_ARG),
+        (_layer(X=P + 1), 0, 10, B.ERR_INVALID_ARG),
+        (_layer(), 10, 10, B.ERR_RANGE),
+        (_layer(), -1, 10, B.ERR_RANGE),
+        (_layer(), 0, 64 * 32 + 1, B.ERR_RANGE),
+        (_layer(out=1 << 40, n_in=1 << 40, ldx=1 << 40, lddy=1 << 40), 0, 10, B.ERR_OVERFLOW),
+    ]
+    for layer, b, e, want in cases:
+        assert lib.chunkft_chunk_wgrad(C.byref(layer), b, e, P, 0, None, 0, None) == want
+        assert lib.chunkft_wgrad_adamw_fused(C.byref(layer), b, e, P, P, P, P, C.byref(hp), None, 0, None) == want
+        assert lib.chunkft_split_k(C.byref(layer), b, e) == want
+        assert lib.chunkft_workspace_bytes(C.byref(layer), b, e) == 0
+    ok = _layer()
+    assert lib.chunkft_chunk_wgrad(C.byref(ok), 0, 10, None, 0, None, 0, None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_chunk_wgrad(C.byref(ok), 0, 10, P, 2, None, 0, None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_wgrad_adamw_fused(C.byref(ok), 0, 10, P, None, P, P, C.byref(hp), None, 0, None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_wgrad_adamw_fused(C.byref(ok), 0, 10, P, P, P, P, None, None, 0, None) == B.ERR_INVALID_ARG
+    # forced split without (enough) workspace
+    sp = _layer(T=64, split_k=2)
+    assert lib.chunkft_split_k(C.byref(sp), 0, 100) == 2
+    assert lib.chunkft_workspace_bytes(C.byref(sp), 0, 100) == 2 * 100 * 4
+    assert lib.chunkft_chunk_wgrad(C.byref(sp), 0, 100, P, 0, None, 0, None) == B.ERR_WORKSPACE
+    assert lib.chunkft_chunk_wgrad(C.byref(sp), 0, 100, P, 0, P, 799, None) == B.ERR_WORKSPACE
+    assert lib.chunkft_chunk_wgrad(C.byref(sp), 0, 100, P, 0, P + 4, 800, None) == B.ERR_WORKSPACE
+    assert lib.chunkft_wgrad_adamw_fused(C.byref(sp), 0, 100, P, P, P, P, C.byref(hp), None, 0, None) == B.ERR_WORKSPACE
+    # AdamW hyper-parameters and sizes
+    for bad in (B.hparams(1e-4, 0.9, 0.999, 1e-8, 0.01, 0), B.hparams(1e-4, 1.0, 0.999, 1e-8, 0.01, 1),
+                B.hparams(1e-4, 0.9, -0.1, 1e-8, 0.01, 1), B.hparams(-1.0, 0.9, 0.999, 1e-8, 0.01, 1),
+                B.hparams(float("nan"), 0.9, 0.999, 1e-8, 0.01, 1)):
+        assert lib.chunkft_adamw_chunk(P, P, P, P, P, B.BF16, 10, C.byref(bad), None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_adamw_chunk(None, P, P, P, P, B.BF16, 10, C.byref(hp), None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_adamw_chunk(P, P, P, P, P, B.BF16, 0, C.byref(hp), None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_adamw_chunk(P, P, P, P, P, 9, 10, C.byref(hp), None) == B.ERR_DTYPE
+    assert lib.chunkft_adamw_chunk(P + 2, P, P, P, P, B.BF16, 10, C.byref(hp), None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_adamw_chunk(P, P, P, P, P + 1, B.BF16, 10, C.byref(hp), None) == B.ERR_INVALID_ARG
+
+
+def test_split_is_a_pure_function_of_shape():
+    lib = B.lib()
+    # 8B up_proj chunk: many tiles, no split
+    big = _layer(out=14336, n_in=4096, T=1024, ldx=4096, lddy=14336)
+    assert lib.chunkft_split_k(C.byref(big), 4097, 4097 + (32 << 20)) == 1
+    # a 2 Mi-element chunk of the lm_head shape at T = 4096: few tiles, split over tokens
+    small = _layer(out=128256, n_in=4096, T=4096, ldx=4096, lddy=128256)
+    s = lib.chunkft_split_k(C.byref(small), 12345, 12345 + (2 << 20))
+    assert 2 <= s <= 64
+    assert lib.chunkft_split_k(C.byref(small), 12345, 12345 + (2 << 20)) == s
+    assert lib.chunkft_workspace_bytes(C.byref(small), 12345, 12345 + (2 << 20)) == s * (2 << 20) * 4
+    # no slab is empty: forcing more slabs than tokens allow is reduced
+    tiny = _layer(T=40, split_k=8)
+    assert lib.chunkft_split_k(C.byref(tiny), 0, 100) == 2      # slabs are whole 32-token tiles: 32 + 8
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2605_21177_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.replace("no fallback", ""), f
