@@ -11,10 +11,10 @@ Comparison rules (the tolerances the build is held to):
   (their update is a difference and may cancel), none for v (a sum of
   non-negative terms);
 * fused path against the full oracle: max|a - b| / max|b| <= 1e-5 for m and v;
-  the same for theta over the elements whose reference gradient is not tiny
-  (|g| >= 1e-4 rms(g)); where it is tiny the first AdamW steps behave like
-  lr * sign(g), which no finite-precision gradient can reproduce, so those
-  elements are only required to move by at most 2 lr (+ 1e-5 |theta|);
+  the same for theta, except that on a cold start (m = v = 0) the step is
+  lr * g / (|g| + eps), a sign function where g is tiny, which no
+  finite-precision gradient can reproduce: elements with |g| < 1e-4 rms(g)
+  are then only required to move by at most 2 lr (+ 1e-5 |theta|);
 * low-precision copy: bit-exact round-to-nearest-even of the GPU's own fp32
   master, and within one bf16 step of the oracle's rounded value;
 * anything outside the chunk: bit-identical to before the call.
@@ -148,11 +148,17 @@ def check_fused_against_oracle(g_ref, th0, m0, v0, hp, step, master, m, v, W_bit
     assert_scale_relative(m, m_ref, "m")
     assert_scale_relative(v, v_ref, "v")
     rms = float(np.sqrt(np.mean(g_ref * g_ref)))
-    well = np.abs(g_ref) >= 1e-4 * rms
+    cold = not (np.any(m0) or np.any(v0))
+    if cold:
+        # from m = v = 0 the step is lr * g / (|g| + eps): a sign function where g is tiny
+        well = np.abs(g_ref) >= 1e-4 * rms
+    else:
+        # warm moments dominate a tiny gradient: every element is well-conditioned
+        well = np.ones(g_ref.shape, dtype=bool)
     assert_scale_relative(master, th_ref, "theta (well-conditioned elements)", mask=well)
     ill = ~well
-    frac = float(ill.mean())
-    assert frac < 1e-3, f"too many tiny-gradient elements: {frac}"
+    # a Gaussian gradient has about 8e-5 of its elements below 1e-4 rms
+    assert ill.sum() <= 3 + 5e-4 * ill.size, f"too many tiny-gradient elements: {int(ill.sum())} of {ill.size}"
     if ill.any():
         moved = np.abs(np.asarray(master, np.float64)[ill] - np.asarray(th0, np.float64)[ill])
         assert np.all(moved <= 2 * hp["lr"] + 1e-5 * np.abs(np.asarray(th0, np.float64)[ill]) + 1e-12)

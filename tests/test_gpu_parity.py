@@ -29,7 +29,7 @@ def _state_for(case, begin, end, rng, warm):
     n = end - begin
     if warm:
         m0 = (rng.standard_normal(n) * 1e-3).astype(np.float32)
-        v0 = (rng.standard_normal(n) ** 2 * 1e-6).astype(np.float32)
+        v0 = ((0.25 + rng.standard_normal(n) ** 2) * 1e-6).astype(np.float32)
     else:
         m0 = np.zeros(n, np.float32)
         v0 = np.zeros(n, np.float32)
