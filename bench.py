@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the ChunkFT hot path on one MI355X.
+
+Workload: benchmark configs[1] -- Llama-3-8B up_proj shape (W 14336 x 4096
+bf16, T = 1024 tokens), one chunk of 32 Mi contiguous elements at a seeded
+mid-row offset, synthetic Gaussian inputs already resident in HBM.
+
+One step = one pass of every stage of the path over that batch:
+  plan      chunkft_plan_cycle on the layer (host, integer)
+  wgrad     chunkft_chunk_wgrad            -> fp32 g[chunk]
+  adamw     chunkft_adamw_chunk            g -> master, m, v, bf16 W   (state set A)
+  fused     chunkft_wgrad_adamw_fused      same update, g never stored  (state set B)
+
+`value` is the chunk-wgrad rate 2*T*E / t(wgrad call) in TFLOP/s; the AdamW
+GB/s (30 B/element) and the fused call are reported beside it.  Kernel times
+are HIP-event brackets on the stream the kernels run on, taken inside the
+timed region.  The CPU baseline is the fp64 oracle on the host cores.
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0        # HBM3E
+
+# HBM bytes per launch from rocprofv3 --pmc runs (FETCH_SIZE / WRITE_SIZE scaled by a
+# copy kernel of known size); None until such a run is summarised under profiles/.
+MEASURED_TRAFFIC = {"wgrad": None, "adamw": None, "fused": None}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the path has no collective); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2605_21177_amd import binding as B
+    from paper_2605_21177_amd import workloads as WL
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.lib()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    case, begin, end = WL.config2()
+    E = end - begin
+    T = case.T
+    X = case.X.to(dev)
+    dY = case.dY.to(dev)
+    layer = B.make_layer(B.LINEAR, X, dY, case.out, case.n_in)
+    S = B.chunkft_split_k(layer, begin, end)
+    ws_bytes = B.chunkft_workspace_bytes(layer, begin, end)
+    ws = torch.empty(max(ws_bytes // 4, 1), dtype=torch.float32, device=dev) if ws_bytes else None
+    tensors = [(case.out, case.n_in, case.dtype, case.kind)]
+    budget = 64 << 20
+
+    W = case.W0.reshape(-1).clone().to(dev)
+    g = torch.empty(E, dtype=torch.float32, device=dev)
+
+    def fresh_state():
+        master = W[begin:end].float()
+        return master, torch.zeros_like(master), torch.zeros_like(master)
+
+    stA = fresh_state()
+    stB = fresh_state()
+    Wa_slice = W.clone()[begin:end]
+    Wb = W.clone()
+    hp = dict(WL.HPARAMS)
+
+    names = ("wgrad", "adamw", "fused")
+    ev = {n: [] for n in names}
+
+    def step(i, record):
+        B.chunkft_plan_cycle(tensors, budget)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if record else None
+        h = B.hparams(step=i + 1, **hp)
+        if record: marks[0].record()
+        B.chunkft_chunk_wgrad(layer, begin, end, g, ws=ws)
+        if record: marks[1].record()
+        B.chunkft_adamw_chunk(g, stA[0], stA[1], stA[2], Wa_slice, E, h)
+        if record: marks[2].record()
+        B.chunkft_wgrad_adamw_fused(layer, begin, end, Wb, stB[0], stB[1], stB[2], h, ws=ws)
+        if record:
+            marks[3].record()
+            for k, n in enumerate(names):
+                ev[n].append((marks[k], marks[k + 1]))
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms = {n: float(np.mean([a.elapsed_time(b) for a, b in ev[n]])) for n in names}
+    ms_med = {n: float(np.median([a.elapsed_time(b) for a, b in ev[n]])) for n in names}
+
+    flops = 2.0 * T * E
+    R = (end - 1) // case.n_in - begin // case.n_in + 1
+    wgrad_bytes = 2.0 * T * case.n_in + 2.0 * T * R + 4.0 * E        # X once, dY columns once, g once
+    adamw_bytes = 30.0 * E                                            # g 4 + state 24 + bf16 W 2
+    fused_bytes = 26.0 * E + 2.0 * T * (case.n_in + R)
+    wgrad_tflops = flops / (ms["wgrad"] * 1e-3) / 1e12
+    adamw_gbps = adamw_bytes / (ms["adamw"] * 1e-3) / 1e9
+    fused_bound_ms = max(flops / (PEAK_BF16_TFLOPS * 1e12), fused_bytes / (PEAK_HBM_GBPS * 1e9)) * 1e3
+
+    out = {
+        "metric": "chunk wgrad TFLOP/s (% MFMA peak) + AdamW GB/s (% HBM) at Llama-3-8B shapes",
+        "value": round(wgrad_tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": "configs[1]: Llama-3-8B up_proj 14336x4096 bf16, T=1024, chunk of 32Mi elements "
+                        f"[{begin},{end}) (row span {R}), fp32 master/m/v for the chunk only",
+            "step": "plan_cycle + chunk_wgrad + adamw_chunk + wgrad_adamw_fused",
+            "split_k": S,
+        },
+        "wgrad": {"ms": round(ms["wgrad"], 4), "ms_median": round(ms_med["wgrad"], 4),
+                  "tflops": round(wgrad_tflops, 2), "pct_mfma_peak": round(100 * wgrad_tflops / PEAK_BF16_TFLOPS, 2)},
+        "adamw": {"ms": round(ms["adamw"], 4), "ms_median": round(ms_med["adamw"], 4),
+                  "gbps": round(adamw_gbps, 1), "pct_hbm_peak": round(100 * adamw_gbps / PEAK_HBM_GBPS, 2)},
+        "fused": {"ms": round(ms["fused"], 4), "ms_median": round(ms_med["fused"], 4),
+                  "bound": "hbm", "bound_ms": round(fused_bound_ms, 4),
+                  "frac_of_bound": round(fused_bound_ms / ms["fused"], 4),
+                  "gbps": round(fused_bytes / (ms["fused"] * 1e-3) / 1e9, 1),
+                  "tflops": round(flops / (ms["fused"] * 1e-3) / 1e12, 2)},
+        "roofline": {"kernel": "wgrad_mfma_kernel (chunkft_chunk_wgrad)", "bound": "mfma",
+                     "achieved": round(wgrad_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(wgrad_tflops / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC["wgrad"],
+                     "algorithmic_bytes": wgrad_bytes},
+        "roofline_adamw": {"kernel": "elementwise_kernel (chunkft_adamw_chunk)", "bound": "hbm",
+                           "achieved": round(adamw_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                           "frac": round(adamw_gbps / PEAK_HBM_GBPS, 4), "traffic": MEASURED_TRAFFIC["adamw"],
+                           "algorithmic_bytes": adamw_bytes},
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(case, begin, end, hp)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(case, begin, end, hp):
+    """The fp64 oracle, as it stands, on the host cores: the gradient of a bounded
+    sample of the same chunk (rows of the chunk's span), then AdamW on it."""
+    import numpy as np
+
+    from oracle import chunkft_oracle as O
+    from paper_2605_21177_amd import workloads as WL
+
+    try:
+        from threadpoolctl import threadpool_info
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        blas_threads = os.cpu_count() or 1
+    X64 = WL.as_f64(case.X)
+    dY64 = WL.as_f64(case.dY)
+    n_in = case.n_in
+    # sample: the whole chunk (about 69 GFLOP of fp64 matmul and a 32 Mi-element AdamW)
+    sample = end - begin
+    b, e = begin, begin + sample
+    t0 = time.perf_counter()
+    g = O.chunk_wgrad(X64, dY64, b, e, dense=False)
+    t1 = time.perf_counter()
+    th0 = WL.as_f64(case.W0).reshape(-1)[b:e]
+    z = np.zeros(sample)
+    O.adamw_step(g, th0, z, z, step=1, **hp)
+    t2 = time.perf_counter()
+    rows = (e - 1) // n_in - b // n_in + 1
+    flops_done = 2.0 * case.T * rows * n_in
+    return {
+        "value": round(2.0 * case.T * sample / (t1 - t0) / 1e12, 5),
+        "unit": "TFLOP/s",
+        "cores": int(blas_threads),
+        "kind": "oracle",
+        "sample": f"the whole chunk, {sample} elements ({rows} rows of fp64 dY^T X via numpy/OpenBLAS, "
+                  f"{flops_done / 1e9:.1f} GFLOP in {t1 - t0:.2f} s), then fp64 AdamW on them in {t2 - t1:.2f} s "
+                  "(numpy element-wise, 1 thread)",
+        "adamw_gbps": round(30.0 * sample / (t2 - t1) / 1e9, 3),
+    }
+
+
+if __name__ == "__main__":
+    main()
