@@ -30,6 +30,17 @@ typedef float f32x4_u __attribute__((ext_vector_type(4), aligned(4)));   // 16 b
 typedef unsigned int u32x2_a8 __attribute__((ext_vector_type(2), aligned(8)));
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 
+// Compile-time loop: the body sees its index as a constant, so register arrays
+// indexed by it never fall back to scratch memory.
+template <int I> struct IntC { static constexpr int value = I; };
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(IntC<I>{});
+    static_for<N, I + 1>(f);
+  }
+}
+
 __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
   unsigned int u = __float_as_uint(f);
   if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);  // quiet NaN
@@ -88,85 +99,101 @@ __device__ __forceinline__ void emit(const Sinks& s, int64_t E, int32_t slab, in
 // bf16 MFMA weight-gradient kernel
 // ---------------------------------------------------------------------------
 // Row decomposition of the chunk [begin, end) of W [out, in]:
-//   body rows [rb0, rb1): complete rows, rb0 a multiple of 8 (16-byte dY loads);
+//   body rows [rb0, rb1): complete rows, rb0 a multiple of 8 (16-byte dY loads),
+//   computed by the MFMA kernel with no range mask beyond the row bound;
 //   edge rows: the partial first row, the up-to-7 complete rows before rb0, and
-//   the partial last row -- at most kMaxEdgeRows of them, computed by FMA.
+//   the partial last row -- at most kMaxEdgeRows of them, computed by the FMA
+//   edge kernel that runs ahead of the MFMA kernel on the same stream.
 struct MfmaParams {
   WgradProblem p;
   int64_t rb0, rb1;
   int32_t tiles_m, tiles_n;
   int32_t n_tile_items;        // tiles_m * tiles_n * S
-  int32_t n_edge_items;        // column blocks of the edge rows (0 if no edge rows)
-  int32_t n_edge_rows;
   int32_t group_m;
-  int64_t edge_row[kMaxEdgeRows];
   Sinks s;
 };
 
-template <int BM_, int BN_, int BK_, int WM_, int WN_>
-struct TileCfg {
-  static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
-  static constexpr int NT = 64 * WM * WN;
-  static constexpr int TM = BM / WM / 32;           // 32x32 blocks per wave along rows
-  static constexpr int TN = BN / WN / 32;
-  static constexpr int LDA = BM + 32;               // +64 B per LDS row: 8 rows of a transpose read hit all banks
-  static constexpr int LDB = BN + 32;
-  static constexpr int STAGE = BK * (LDA + LDB);    // bf16 elements per stage
-  static constexpr int CA = BK * BM / 8 / NT;       // 16-byte pieces per thread per stage
-  static constexpr int CB = BK * BN / 8 / NT;
-  static constexpr int EDGE_COLS = 128;
-  static constexpr int TG = NT / 64;                // token groups of the edge path
-  static constexpr size_t LDS_MAIN = 2 * STAGE * 2;
-  static constexpr size_t LDS_EDGE = (size_t)TG * kMaxEdgeRows * EDGE_COLS * 4;
-  static constexpr size_t LDS_BYTES = LDS_MAIN > LDS_EDGE ? LDS_MAIN : LDS_EDGE;
-  static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 16 == 0, "tile shape");
-  static_assert((BK * BM / 8) % NT == 0 && (BK * BN / 8) % NT == 0, "loader shape");
+struct EdgeParams {
+  WgradProblem p;
+  int64_t lead_base;   // first row of the 8-row group that holds the leading edge rows, or -1
+  int64_t trail_row;   // the partial last row, or -1
+  Sinks s;
 };
 
-template <class C, int MODE>
-__device__ __forceinline__ void edge_item(const MfmaParams& q, int item, unsigned short* lds_raw) {
-  // One block of EDGE_COLS columns, all edge rows at once: every thread owns two
-  // adjacent columns and a residue class of tokens; partial sums meet in LDS and
-  // are added in token-group order.
+// Tile configuration of the MFMA kernel: a 256 x 256 output tile per workgroup
+// of 8 waves (2 x 4, each wave 128 x 64 = 4 x 2 blocks of 32 x 32), tokens in
+// slabs of 32, and a ring of NS slabs in LDS filled by global->LDS loads.
+template <int NS_>
+struct RingCfg {
+  static constexpr int BM = 256, BN = 256, BK = 32, WM = 2, WN = 4, NS = NS_;
+  static constexpr int NW = WM * WN, NT = 64 * NW;
+  static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  static constexpr int A_BYTES = BK * BM * 2, B_BYTES = BK * BN * 2;
+  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  static constexpr int LA = A_BYTES / 1024 / NW;     // 1 KB wave-loads per wave per slab
+  static constexpr int LB = B_BYTES / 1024 / NW;
+  static constexpr int L = LA + LB;
+  static constexpr size_t LDS_BYTES = (size_t)NS * STAGE_BYTES;
+  static_assert(TM == 4 && TN == 2 && L == 4 && NS >= 3, "the main loop is written out for this shape");
+};
+
+// Edge rows: the leading ones all lie in one 8-aligned group of rows (one 16-byte
+// piece of dY per token), the trailing one is a single row.  One workgroup per
+// 32 columns; thread (tg, c) owns column c and the tokens t = tg (mod 32).  The
+// loads of kEdgeUnroll tokens are issued together, so a trip costs one memory
+// latency.  The 32 token-group partials meet in LDS and are added in group order.
+constexpr int kEdgeCols = 32;
+constexpr int kEdgeTG = 32;
+constexpr int kEdgeThreads = kEdgeCols * kEdgeTG;
+constexpr int kEdgeUnroll = 8;
+
+template <int MODE>
+__global__ __launch_bounds__(kEdgeThreads) void wgrad_edge_kernel(const EdgeParams q) {
+  __shared__ float red[kEdgeTG][kMaxEdgeRows][kEdgeCols];
   const WgradProblem& p = q.p;
-  float* red = reinterpret_cast<float*>(lds_raw);           // [TG][kMaxEdgeRows][EDGE_COLS]
-  const int lane = threadIdx.x & 63;
-  const int tg = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t c = (int64_t)item * C::EDGE_COLS + lane * 2;
+  const int c = threadIdx.x & (kEdgeCols - 1), tg = threadIdx.x / kEdgeCols;
+  const int64_t col = (int64_t)blockIdx.x * kEdgeCols + c;
+  const bool col_ok = col < p.in;
   const unsigned short* X = (const unsigned short*)p.X;
   const unsigned short* dY = (const unsigned short*)p.dY;
-  float acc[kMaxEdgeRows][2];
+  const bool has_lead = q.lead_base >= 0, has_trail = q.trail_row >= 0;
+  float acc[kMaxEdgeRows];
 #pragma unroll
-  for (int e = 0; e < kMaxEdgeRows; ++e) acc[e][0] = acc[e][1] = 0.f;
-  if (c < p.in) {                                           // in % 8 == 0: both columns valid
-    for (int64_t t = tg; t < p.T; t += C::TG) {
-      const unsigned int xx = *(const unsigned int*)(X + t * p.ldx + c);
-      const float x0 = __uint_as_float(xx << 16), x1 = __uint_as_float(xx & 0xffff0000u);
+  for (int e = 0; e < kMaxEdgeRows; ++e) acc[e] = 0.f;
+  for (int64_t t0 = tg; t0 < p.T; t0 += (int64_t)kEdgeTG * kEdgeUnroll) {
+    unsigned short xs[kEdgeUnroll], tr[kEdgeUnroll];
+    uint4 ld[kEdgeUnroll];
 #pragma unroll
-      for (int e = 0; e < kMaxEdgeRows; ++e) {
-        if (e < q.n_edge_rows) {
-          const float d = bf16_bits_to_f32(dY[t * p.lddy + q.edge_row[e]]);
-          acc[e][0] = fmaf(d, x0, acc[e][0]);
-          acc[e][1] = fmaf(d, x1, acc[e][1]);
-        }
+    for (int u = 0; u < kEdgeUnroll; ++u) {
+      const int64_t t = t0 + (int64_t)u * kEdgeTG;
+      const bool ok = t < p.T && col_ok;
+      xs[u] = ok ? X[t * p.ldx + col] : (unsigned short)0;
+      ld[u] = (ok && has_lead) ? *(const uint4*)(dY + t * p.lddy + q.lead_base) : make_uint4(0, 0, 0, 0);
+      tr[u] = (ok && has_trail) ? dY[t * p.lddy + q.trail_row] : (unsigned short)0;
+    }
+#pragma unroll
+    for (int u = 0; u < kEdgeUnroll; ++u) {
+      const float x = bf16_bits_to_f32(xs[u]);
+      const unsigned int w[4] = {ld[u].x, ld[u].y, ld[u].z, ld[u].w};
+#pragma unroll
+      for (int h = 0; h < 4; ++h) {
+        acc[2 * h] = fmaf(__uint_as_float(w[h] << 16), x, acc[2 * h]);
+        acc[2 * h + 1] = fmaf(__uint_as_float(w[h] & 0xffff0000u), x, acc[2 * h + 1]);
       }
+      acc[8] = fmaf(bf16_bits_to_f32(tr[u]), x, acc[8]);
     }
   }
 #pragma unroll
-  for (int e = 0; e < kMaxEdgeRows; ++e) {
-    red[(tg * kMaxEdgeRows + e) * C::EDGE_COLS + lane * 2 + 0] = acc[e][0];
-    red[(tg * kMaxEdgeRows + e) * C::EDGE_COLS + lane * 2 + 1] = acc[e][1];
-  }
+  for (int e = 0; e < kMaxEdgeRows; ++e) red[tg][e][c] = acc[e];
   __syncthreads();
-  const int64_t E = p.end - p.begin;
-  for (int idx = threadIdx.x; idx < q.n_edge_rows * C::EDGE_COLS; idx += C::NT) {
-    const int e = idx / C::EDGE_COLS, cc = idx % C::EDGE_COLS;
-    const int64_t col = (int64_t)item * C::EDGE_COLS + cc;
-    const int64_t flat = q.edge_row[e] * p.in + col;
-    if (col < p.in && flat >= p.begin && flat < p.end) {
-      float sum = red[(0 * kMaxEdgeRows + e) * C::EDGE_COLS + cc];
-      for (int g = 1; g < C::TG; ++g) sum += red[(g * kMaxEdgeRows + e) * C::EDGE_COLS + cc];
-      const int64_t i = flat - p.begin;
+  if (threadIdx.x < kMaxEdgeRows * kEdgeCols && col_ok) {
+    const int e = threadIdx.x / kEdgeCols;
+    const int64_t row = e < 8 ? q.lead_base + e : q.trail_row;
+    const int64_t flat = row * p.in + col;
+    if (row >= 0 && flat >= p.begin && flat < p.end) {
+      float sum = red[0][e][c];
+      for (int g = 1; g < kEdgeTG; ++g) sum += red[g][e][c];
+      const int64_t E = p.end - p.begin, i = flat - p.begin;
       if constexpr (MODE == EMIT_PARTIAL) {
         // the edge rows take all tokens at once: slab 0 carries the sum, the rest zero
         q.s.ws[i] = sum;
@@ -178,22 +205,58 @@ __device__ __forceinline__ void edge_item(const MfmaParams& q, int item, unsigne
   }
 }
 
+#define GLB_PTR(T) __attribute__((address_space(1))) T*
+
+// LDS transpose read issued as opaque assembly: the compiler must not know that
+// it reads LDS, or it would wait for every outstanding global->LDS load before
+// it.  The counterpart is that waiting for its result is also done by hand
+// (WAIT_HALVES below).
+template <int OFF>
+__device__ __forceinline__ bf16x4 lds_tr_read(unsigned addr) {
+  bf16x4 r;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF) : "memory");
+  return r;
+}
+// s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, others "no wait")
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | (7 << 4) | (0xF << 8) | ((N >> 4) << 14));
+}
+#define WAIT_HALVES(h)                                                                                   \
+  asm volatile("s_waitcnt lgkmcnt(0)"                                                                    \
+               : "+v"(h[0]), "+v"(h[1]), "+v"(h[2]), "+v"(h[3]), "+v"(h[4]), "+v"(h[5]), "+v"(h[6]),     \
+                 "+v"(h[7]), "+v"(h[8]), "+v"(h[9]), "+v"(h[10]), "+v"(h[11])::"memory")
+
+// One 256 x 256 tile of body rows over one slab of tokens.
+//
+// Data movement.  dY and X are [token][row] / [token][column]: both operands have
+// the contraction index outermost, the opposite of what an MFMA lane wants (8
+// consecutive tokens of one row).  A slab of 32 tokens x 256 rows is copied as it
+// is (512 B per token) into LDS by global_load_lds_dwordx4 -- no VGPR staging, up
+// to NS-1 slabs in flight -- and transposed on the way out by ds_read_b64_tr_b16.
+// A wave-load writes 1 KB = tokens 2j, 2j+1; lane l lands in token 2j + l/32,
+// physical 16-byte slot l%32.  To keep the 8 tokens that one transpose read
+// touches on different banks, slot s of token k holds logical slot
+// s ^ (sw(k) << 2), sw(k) = (k & 3) | ((k >> 3 & 1) << 2): the swizzle is applied
+// to the GLOBAL address each lane fetches, LDS writes stay linear.
+//
+// Schedule.  Per 32-token slab a wave issues 16 MFMAs in two 16-token steps.
+// After every pair of MFMAs it issues three transpose reads for the NEXT step
+// and, in the first step, one global->LDS load of a later slab, so LDS, the
+// vector-memory pipe and the matrix pipe are all fed evenly instead of in bursts.
+// One s_barrier per slab: it publishes slab kt+1 (every wave waited for its own
+// loads of it) and retires slab kt-1, whose buffer the new loads overwrite.
 template <class C, int MODE>
 __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
-  extern __shared__ __attribute__((aligned(16))) unsigned short lds[];
+  extern __shared__ __attribute__((aligned(1024))) unsigned char ldsb[];
   const WgradProblem& p = q.p;
 
   // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD one
   // contiguous run of work items so that tiles sharing dY rows / X columns
   // meet in the same L2.
-  const int n_items = q.n_tile_items + q.n_edge_items;
+  const int n_items = q.n_tile_items;
   const int per_xcd = (n_items + 7) >> 3;
   const int item = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
   if (item >= n_items) return;
-  if (item >= q.n_tile_items) {
-    edge_item<C, MODE>(q, item - q.n_tile_items, lds);
-    return;
-  }
 
   // ---- which tile, which token slab
   const int n_tiles = q.tiles_m * q.tiles_n;
@@ -210,62 +273,117 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   const int64_t col0 = (int64_t)tile_n * C::BN;
   const int64_t k_begin = (int64_t)slab * p.kslab;
   const int64_t k_end = (k_begin + p.kslab < p.T) ? k_begin + p.kslab : p.T;
-  const int nk = (int)((k_end - k_begin + C::BK - 1) / C::BK);
+  const int klen = (int)(k_end - k_begin);
+  const int nk = (klen + C::BK - 1) / C::BK;
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm0 = (wave / C::WN) * (C::BM / C::WM);
   const int wn0 = (wave % C::WN) * (C::BN / C::WN);
-
   const unsigned short* dY = (const unsigned short*)p.dY;
   const unsigned short* X = (const unsigned short*)p.X;
+  const unsigned lds_base = (unsigned)(uintptr_t)ldsb;
 
-  // ---- global -> register staging: 16-byte pieces, rows of the tile contiguous
-  uint4 ra[C::CA], rb[C::CB];
-  auto fetch = [&](int kt) {
-    const int64_t k0 = k_begin + (int64_t)kt * C::BK;
+  // ---- global->LDS loads: per-lane source pointers that advance one slab per fetch.
+  // Rows / columns past the tensor are redirected to the tile's first ones (valid
+  // memory, results masked in the epilogue); tokens past the end are clamped to
+  // the last token and zeroed in the A fragments (mask_halves).
+  const unsigned short* ga[C::LA];
+  const unsigned short* gb[C::LB];
+  const unsigned short* pa[C::LA];
+  const unsigned short* pb[C::LB];
+  int ka[C::LA], kb[C::LB];
 #pragma unroll
-    for (int i = 0; i < C::CA; ++i) {
-      const int id = tid + i * C::NT;
-      const int kr = id / (C::BM / 8), mc = id % (C::BM / 8);
-      const int64_t t = k0 + kr, r = row0 + mc * 8;
-      ra[i] = (t < k_end && r < p.out) ? *(const uint4*)(dY + t * p.lddy + r) : make_uint4(0, 0, 0, 0);
-    }
+  for (int i = 0; i < C::LA; ++i) {
+    const int k = 2 * (wave * C::LA + i) + (lane >> 5);
+    const int lc = (lane & 31) ^ (((k & 3) | (((k >> 3) & 1) << 2)) << 2);
+    int64_t r = row0 + lc * 8;
+    if (r >= p.out) r = row0;
+    ka[i] = k;
+    ga[i] = dY + r;
+    pa[i] = ga[i] + (k_begin + k) * p.lddy;
+  }
 #pragma unroll
-    for (int i = 0; i < C::CB; ++i) {
-      const int id = tid + i * C::NT;
-      const int kr = id / (C::BN / 8), nc = id % (C::BN / 8);
-      const int64_t t = k0 + kr, cc = col0 + nc * 8;
-      rb[i] = (t < k_end && cc < p.in) ? *(const uint4*)(X + t * p.ldx + cc) : make_uint4(0, 0, 0, 0);
+  for (int i = 0; i < C::LB; ++i) {
+    const int k = 2 * (wave * C::LB + i) + (lane >> 5);
+    const int lc = (lane & 31) ^ (((k & 3) | (((k >> 3) & 1) << 2)) << 2);
+    int64_t cc = col0 + lc * 8;
+    if (cc >= p.in) cc = col0;
+    kb[i] = k;
+    gb[i] = X + cc;
+    pb[i] = gb[i] + (k_begin + k) * p.ldx;
+  }
+  const int64_t stepA = (int64_t)C::BK * p.lddy, stepB = (int64_t)C::BK * p.ldx;
+  int next_fetch = 0;   // slab index the pointers stand at
+  auto issue_one = [&](auto idxc) {
+    constexpr int idx = decltype(idxc)::value;
+    const int stage = next_fetch % C::NS;
+    const bool ragged = (next_fetch + 1) * C::BK > klen;     // only the last slab can be
+    if constexpr (idx < C::LA) {
+      constexpr int i = idx;
+      const unsigned short* src = pa[i];
+      if (ragged) {
+        int64_t t = k_begin + (int64_t)next_fetch * C::BK + ka[i];
+        if (t > p.T - 1) t = p.T - 1;
+        src = ga[i] + t * p.lddy;
+      }
+      const unsigned dst = lds_base + stage * C::STAGE_BYTES + (wave * C::LA + i) * 1024;
+      __builtin_amdgcn_global_load_lds((GLB_PTR(const void))src, (LDS_PTR(void))(uintptr_t)dst, 16, 0, 0);
+      pa[i] += stepA;
+    } else {
+      constexpr int i = idx - C::LA;
+      const unsigned short* src = pb[i];
+      if (ragged) {
+        int64_t t = k_begin + (int64_t)next_fetch * C::BK + kb[i];
+        if (t > p.T - 1) t = p.T - 1;
+        src = gb[i] + t * p.ldx;
+      }
+      const unsigned dst = lds_base + stage * C::STAGE_BYTES + C::A_BYTES + (wave * C::LB + i) * 1024;
+      __builtin_amdgcn_global_load_lds((GLB_PTR(const void))src, (LDS_PTR(void))(uintptr_t)dst, 16, 0, 0);
+      pb[i] += stepB;
     }
   };
-  auto stash = [&](int stage) {
-    unsigned short* A = lds + stage * C::STAGE;
-    unsigned short* B = A + C::BK * C::LDA;
-#pragma unroll
-    for (int i = 0; i < C::CA; ++i) {
-      const int id = tid + i * C::NT;
-      const int kr = id / (C::BM / 8), mc = id % (C::BM / 8);
-      *(uint4*)(A + kr * C::LDA + mc * 8) = ra[i];
-    }
-#pragma unroll
-    for (int i = 0; i < C::CB; ++i) {
-      const int id = tid + i * C::NT;
-      const int kr = id / (C::BN / 8), nc = id % (C::BN / 8);
-      *(uint4*)(B + kr * C::LDB + nc * 8) = rb[i];
-    }
-  };
 
-  // ---- LDS transpose-read addressing.  In a block of 16 lanes, lane j reads 4
+  // ---- transpose-read addressing.  In a block of 16 lanes, lane j reads 4
   // consecutive row indices of token (j / 4); the instruction hands lane i the 4
   // tokens of row index i.  Lanes 0-31 take tokens 0-7 of a 16-token step, lanes
-  // 32-63 tokens 8-15: exactly the operand layout of the 32x32x16 MFMA.
+  // 32-63 tokens 8-15: the operand layout of the 32x32x16 MFMA.  The swizzle
+  // term of a lane is the same for every step: sw = (i16 / 4) | ((blk / 2) << 2).
   const int blk = lane >> 4, i16 = lane & 15;
   const int tr_k = (blk >> 1) * 8 + (i16 >> 2);
-  const int tr_m = (blk & 1) * 16 + (i16 & 3) * 4;
-  const int offA = tr_k * C::LDA + wm0 + tr_m;
-  const int offB = tr_k * C::LDB + wn0 + tr_m;
+  const int swl = (i16 >> 2) | ((blk >> 1) << 2);
+  const int low = (blk & 1) * 2 + ((i16 & 3) >> 1);     // low two bits of the 16-byte slot index
+  const int sub = (i16 & 1) * 8;                        // byte offset inside the slot
+  unsigned addrA[C::TM], addrB[C::TN];
+#pragma unroll
+  for (int a = 0; a < C::TM; ++a)
+    addrA[a] = lds_base + tr_k * 512 + ((((wm0 >> 3) + a * 4) ^ (swl << 2)) + low) * 16 + sub;
+#pragma unroll
+  for (int b = 0; b < C::TN; ++b)
+    addrB[b] = lds_base + C::A_BYTES + tr_k * 512 + ((((wn0 >> 3) + b * 4) ^ (swl << 2)) + low) * 16 + sub;
+
+  // Fragment halves: unit u < 8 is A block u/2 (tokens 0-3 | 8-11 if u is even,
+  // 4-7 | 12-15 if odd), unit u >= 8 is B block (u-8)/2 likewise.
+  bf16x4 h0[12], h1[12];
+  auto read_unit = [&](bf16x4* h, unsigned so, auto ksc, auto uc) {
+    constexpr int ks = decltype(ksc)::value, u = decltype(uc)::value;
+    constexpr int off = (ks * 16 + (u & 1) * 4) * 512;
+    if constexpr (u < 8) h[u] = lds_tr_read<off>(addrA[u / 2] + so);
+    else h[u] = lds_tr_read<off>(addrB[(u - 8) / 2] + so);
+  };
+  auto frag = [&](const bf16x4* h, int u) {
+    return __builtin_shufflevector(h[u], h[u + 1], 0, 1, 2, 3, 4, 5, 6, 7);
+  };
+  auto mask_halves = [&](bf16x4* h, int kt, int ks) {
+    if (kt == nk - 1 && (klen % C::BK) != 0) {
+      const int kv = klen - kt * C::BK - ks * 16 - (lane >> 5) * 8;   // valid tokens among this lane's 8
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if ((u & 1) * 4 + e >= kv) h[u][e] = (__bf16)0.f;
+    }
+  };
 
   f32x16 acc[C::TM][C::TN];
 #pragma unroll
@@ -275,60 +393,130 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-  fetch(0);
-  stash(0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk) fetch(kt + 1);
-    const unsigned short* A = lds + (kt & 1) * C::STAGE;
-    const unsigned short* B = A + C::BK * C::LDA;
+  // ---- prologue: NS-1 slabs in flight, first step of slab 0 in registers
 #pragma unroll
-    for (int ks = 0; ks < C::BK / 16; ++ks) {
-      bf16x8 fa[C::TM], fb[C::TN];
-#pragma unroll
-      for (int a = 0; a < C::TM; ++a) {
-        const unsigned short* src = A + offA + (ks * 16) * C::LDA + a * 32;
-        bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(src));
-        bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(src + 4 * C::LDA));
-        fa[a] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      }
-#pragma unroll
-      for (int b = 0; b < C::TN; ++b) {
-        const unsigned short* src = B + offB + (ks * 16) * C::LDB + b * 32;
-        bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(src));
-        bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(src + 4 * C::LDB));
-        fb[b] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      }
-#pragma unroll
-      for (int a = 0; a < C::TM; ++a)
-#pragma unroll
-        for (int b = 0; b < C::TN; ++b)
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+  for (int s = 0; s < C::NS - 1; ++s)
+    if (s < nk) {
+      static_for<C::L>([&](auto ic) { issue_one(ic); });
+      ++next_fetch;
     }
-    if (kt + 1 < nk) stash((kt + 1) & 1);
-    __syncthreads();
+  if (C::NS - 2 < nk) wait_vmcnt<(C::NS - 2) * C::L>(); else wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
+  static_for<12>([&](auto uc) { read_unit(h0, 0u, IntC<0>{}, uc); });
+  WAIT_HALVES(h0);
+  mask_halves(h0, 0, 0);
+
+  for (int kt = 0; kt < nk; ++kt) {
+    // slab kt+1 has landed once at most the NS-3 younger slabs are outstanding
+    if (kt + C::NS - 2 < nk) wait_vmcnt<(C::NS - 3) * C::L>(); else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    const bool fetch = kt + C::NS - 1 < nk;
+    const bool more = kt + 1 < nk;
+    const unsigned so = (unsigned)((kt % C::NS) * C::STAGE_BYTES);
+    const unsigned so_next = (unsigned)(((kt + 1) % C::NS) * C::STAGE_BYTES);
+    static_for<4>([&](auto ac) {
+      constexpr int a = decltype(ac)::value;
+      __builtin_amdgcn_sched_barrier(0);
+      acc[a][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h0, 2 * a), frag(h0, 8), acc[a][0], 0, 0, 0);
+      acc[a][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h0, 2 * a), frag(h0, 10), acc[a][1], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      read_unit(h1, so, IntC<1>{}, IntC<3 * a>{});
+      read_unit(h1, so, IntC<1>{}, IntC<3 * a + 1>{});
+      read_unit(h1, so, IntC<1>{}, IntC<3 * a + 2>{});
+      if (fetch) issue_one(ac);
+    });
+    if (fetch) ++next_fetch;
+    __builtin_amdgcn_sched_barrier(0);
+    WAIT_HALVES(h1);
+    mask_halves(h1, kt, 1);
+    static_for<4>([&](auto ac) {
+      constexpr int a = decltype(ac)::value;
+      __builtin_amdgcn_sched_barrier(0);
+      acc[a][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h1, 2 * a), frag(h1, 8), acc[a][0], 0, 0, 0);
+      acc[a][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h1, 2 * a), frag(h1, 10), acc[a][1], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (more) {
+        read_unit(h0, so_next, IntC<0>{}, IntC<3 * a>{});
+        read_unit(h0, so_next, IntC<0>{}, IntC<3 * a + 1>{});
+        read_unit(h0, so_next, IntC<0>{}, IntC<3 * a + 2>{});
+      }
+    });
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) {
+      WAIT_HALVES(h0);
+      mask_halves(h0, kt + 1, 0);
+    }
   }
 
   // ---- epilogue.  Accumulator register v of a 32x32 block holds
   // row (v / 4) * 8 + (lane / 32) * 4 + v % 4, column lane % 32: for a fixed
   // register a half-wave covers 32 consecutive columns of one row (128 B of fp32).
+  // Everything is addressed as one uniform 64-bit tile origin plus a 32-bit
+  // offset (the host admits only in < 2^21, so 256 rows stay below 2^31 bytes).
   const int64_t E = p.end - p.begin;
-  const bool interior = (row0 + C::BM <= q.rb1) && (col0 + C::BN <= p.in);
+  const int64_t origin = row0 * p.in + col0 - p.begin;             // chunk-local index of the tile corner
+  const unsigned in_u = (unsigned)p.in;
+  const unsigned lane_off = (unsigned)(wm0 + (lane >> 5) * 4) * in_u + (unsigned)(wn0 + (lane & 31));
+  const int rows_valid = (int)((q.rb1 - row0 < C::BM) ? q.rb1 - row0 : C::BM);
+  const int cols_valid = (int)((p.in - col0 < C::BN) ? p.in - col0 : C::BN);
+  const bool interior = rows_valid == C::BM && cols_valid == C::BN;
+  float* const dst = MODE == EMIT_PARTIAL ? q.s.ws + (int64_t)slab * E + origin
+                   : (MODE == EMIT_ADAMW ? q.s.master + origin : q.s.g + origin);
+  float* const m_t = q.s.m + origin;
+  float* const v_t = q.s.v + origin;
+  unsigned short* const w16 = (unsigned short*)q.s.W + origin + p.begin;
+  float* const w32 = (float*)q.s.W + origin + p.begin;
+  static_for<C::TM * C::TN>([&](auto blk_c) {
+    constexpr int a = decltype(blk_c)::value / C::TN, b = decltype(blk_c)::value % C::TN;
+    const unsigned blk_off = lane_off + (unsigned)(a * 32) * in_u + (unsigned)(b * 32);
+    __builtin_amdgcn_sched_barrier(0);      // one block at a time: bounds the registers the epilogue holds
+    if (interior) {
+      if constexpr (MODE == EMIT_ADAMW) {
+        // all state loads of the block first (48 independent loads per lane), then
+        // the arithmetic, then the stores: the update is bound by HBM, not by latency
+        f32x16 th, mm, vv;
 #pragma unroll
-  for (int a = 0; a < C::TM; ++a) {
+        for (int v = 0; v < 16; ++v) {
+          const unsigned o = blk_off + (unsigned)((v >> 2) * 8 + (v & 3)) * in_u;
+          th[v] = dst[o];
+          mm[v] = m_t[o];
+          vv[v] = v_t[o];
+        }
 #pragma unroll
-    for (int b = 0; b < C::TN; ++b) {
-      const int64_t col = col0 + wn0 + b * 32 + (lane & 31);
+        for (int v = 0; v < 16; ++v) {
+          float t = th[v], x = mm[v], y = vv[v];
+          adamw_update(acc[a][b][v], t, x, y, q.s.c);
+          th[v] = t; mm[v] = x; vv[v] = y;
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const unsigned o = blk_off + (unsigned)((v >> 2) * 8 + (v & 3)) * in_u;
+          dst[o] = th[v];
+          m_t[o] = mm[v];
+          v_t[o] = vv[v];
+          if (q.s.w_kind == W_BF16) w16[o] = f32_to_bf16_rne(th[v]);
+          else if (q.s.w_kind == W_F32) w32[o] = th[v];
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const unsigned o = blk_off + (unsigned)((v >> 2) * 8 + (v & 3)) * in_u;
+          if constexpr (MODE == EMIT_ACCUM) dst[o] += acc[a][b][v];
+          else dst[o] = acc[a][b][v];
+        }
+      }
+    } else {
+      const int lc = wn0 + b * 32 + (lane & 31);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int64_t row = row0 + wm0 + a * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-        if (interior || (row < q.rb1 && col < p.in)) {
-          const int64_t flat = row * p.in + col;
-          emit<MODE>(q.s, E, slab, flat - p.begin, flat, acc[a][b][v]);
+        const int lr = wm0 + a * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        if (lr < rows_valid && lc < cols_valid) {
+          const int64_t i = origin + (int64_t)lr * p.in + lc;
+          emit<MODE>(q.s, E, slab, i, i + p.begin, acc[a][b][v]);
         }
       }
     }
-  }
+  });
 }
 
 // ---------------------------------------------------------------------------
@@ -528,34 +716,30 @@ constexpr int kNumCU = 256;
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-using MainCfg = TileCfg<256, 256, 32, 2, 4>;   // 512 threads, wave tile 128 x 64
+using MainCfg = RingCfg<4>;   // four slabs of 32 KB in LDS
 
 struct RowSplit {
-  int64_t rb0, rb1;
-  int n_edge;
-  int64_t edge_row[kMaxEdgeRows];
+  int64_t rb0, rb1;     // MFMA body rows [rb0, rb1), empty if rb1 <= rb0
+  int64_t lead_base;    // 8-aligned group holding the leading edge rows, or -1
+  int64_t trail_row;    // partial last row outside the body, or -1
 };
 
+// Body = complete rows from the first multiple of 8 on.  Everything before it
+// lies in the one 8-row group [rb0 - 8, rb0) (at most the partial first row and
+// 7 complete rows); after it there is at most the partial last row.
 RowSplit split_rows(const WgradProblem& p) {
   RowSplit rs{};
   const int64_t r0 = p.begin / p.in, c0 = p.begin % p.in;
   const int64_t r1 = (p.end - 1) / p.in, c1 = (p.end - 1) % p.in + 1;
   const int64_t full0 = r0 + (c0 != 0 ? 1 : 0);           // first complete row
   const int64_t full1 = r1 + 1 - (c1 != p.in ? 1 : 0);    // one past the last complete row
-  int64_t rb0 = (full0 + 7) / 8 * 8;
-  int64_t rb1 = full1;
-  if (rb1 <= rb0) { rb0 = rb1 = 0; }
+  const int64_t rb0 = (full0 + 7) / 8 * 8;
+  const bool body = full1 > rb0;
   rs.rb0 = rb0;
-  rs.rb1 = rb1;
-  // edge rows: everything in [r0, r1] outside [rb0, rb1)
-  int n = 0;
-  if (rb1 > rb0) {
-    for (int64_t r = r0; r < rb0; ++r) rs.edge_row[n++] = r;
-    for (int64_t r = rb1; r <= r1; ++r) rs.edge_row[n++] = r;
-  } else {
-    for (int64_t r = r0; r <= r1; ++r) rs.edge_row[n++] = r;   // caller guarantees <= kMaxEdgeRows
-  }
-  rs.n_edge = n;
+  rs.rb1 = body ? full1 : rb0;
+  rs.lead_base = r0 < rb0 ? rb0 - 8 : -1;
+  const int64_t first_after = body ? full1 : rb0;          // rows from here on are not in the lead group
+  rs.trail_row = r1 >= first_after ? r1 : -1;
   return rs;
 }
 
@@ -578,12 +762,7 @@ bool mfma_path_ok(const WgradProblem& p) {
   const auto a16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
   if (!(p.in % 8 == 0 && p.out % 8 == 0 && p.ldx % 8 == 0 && p.lddy % 8 == 0 && a16(p.X) && a16(p.dY)))
     return false;
-  // rows outside the 8-aligned body must fit the edge path
-  const int64_t r0 = p.begin / p.in, r1 = (p.end - 1) / p.in;
-  const int64_t c0 = p.begin % p.in, c1 = (p.end - 1) % p.in + 1;
-  const int64_t full0 = r0 + (c0 != 0 ? 1 : 0), full1 = r1 + 1 - (c1 != p.in ? 1 : 0);
-  const int64_t rb0 = (full0 + 7) / 8 * 8;
-  if (full1 <= rb0) return (r1 - r0 + 1) <= kMaxEdgeRows;
+  if (p.in >= (1 << 21)) return false;      // the epilogue's 32-bit tile offsets
   return true;
 }
 
@@ -611,30 +790,48 @@ Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T
   return {(int32_t)S, kslab};
 }
 
-int launch_wgrad_bf16_mfma(const WgradProblem& p, int mode, const Sinks& s, void* stream) {
-  using C = MainCfg;
+template <class C>
+int launch_mfma_cfg(const WgradProblem& p, int mode, const Sinks& s, hipStream_t st) {
+  const RowSplit rs = split_rows(p);
+  if (rs.lead_base >= 0 || rs.trail_row >= 0) {
+    EdgeParams e{};
+    e.p = p;
+    e.s = s;
+    e.lead_base = rs.lead_base;
+    e.trail_row = rs.trail_row;
+    const dim3 grid((unsigned)ceil_div(p.in, kEdgeCols)), block(kEdgeThreads);
+    switch (mode) {
+      case EMIT_STORE: hipLaunchKernelGGL((wgrad_edge_kernel<EMIT_STORE>), grid, block, 0, st, e); break;
+      case EMIT_ACCUM: hipLaunchKernelGGL((wgrad_edge_kernel<EMIT_ACCUM>), grid, block, 0, st, e); break;
+      case EMIT_PARTIAL: hipLaunchKernelGGL((wgrad_edge_kernel<EMIT_PARTIAL>), grid, block, 0, st, e); break;
+      default: hipLaunchKernelGGL((wgrad_edge_kernel<EMIT_ADAMW>), grid, block, 0, st, e); break;
+    }
+    const int err = (int)hipGetLastError();
+    if (err != 0) return err;
+  }
+  if (rs.rb1 <= rs.rb0) return 0;
   MfmaParams q{};
   q.p = p;
   q.s = s;
-  const RowSplit rs = split_rows(p);
   q.rb0 = rs.rb0;
   q.rb1 = rs.rb1;
-  q.n_edge_rows = rs.n_edge;
-  for (int e = 0; e < kMaxEdgeRows; ++e) q.edge_row[e] = e < rs.n_edge ? rs.edge_row[e] : 0;
   q.tiles_m = (int32_t)ceil_div(rs.rb1 - rs.rb0, C::BM);
   q.tiles_n = (int32_t)ceil_div(p.in, C::BN);
-  q.n_tile_items = q.tiles_m * q.tiles_n * p.S;
-  q.n_edge_items = rs.n_edge > 0 ? (int32_t)ceil_div(p.in, C::EDGE_COLS) : 0;
+  const int64_t n_items = (int64_t)q.tiles_m * q.tiles_n * p.S;
+  if (n_items > 0x3fffffff) return (int)hipErrorInvalidValue;
+  q.n_tile_items = (int32_t)n_items;
   q.group_m = 8;
-  const int n_items = q.n_tile_items + q.n_edge_items;
-  const int grid = (n_items + 7) / 8 * 8;
-  hipStream_t st = (hipStream_t)stream;
+  const int grid = (q.n_tile_items + 7) / 8 * 8;
   switch (mode) {
     case EMIT_STORE: return launch_mfma_mode<C, EMIT_STORE>(q, grid, st);
     case EMIT_ACCUM: return launch_mfma_mode<C, EMIT_ACCUM>(q, grid, st);
     case EMIT_PARTIAL: return launch_mfma_mode<C, EMIT_PARTIAL>(q, grid, st);
     default: return launch_mfma_mode<C, EMIT_ADAMW>(q, grid, st);
   }
+}
+
+int launch_wgrad_bf16_mfma(const WgradProblem& p, int mode, const Sinks& s, void* stream) {
+  return launch_mfma_cfg<MainCfg>(p, mode, s, (hipStream_t)stream);
 }
 
 template <typename T>
