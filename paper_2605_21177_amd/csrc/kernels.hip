@@ -61,13 +61,16 @@ template <> __device__ __forceinline__ float load_as_f32<unsigned short>(const u
 // One AdamW update in fp32 (Algorithm 1 lines 19-21).  Every path that updates
 // state goes through this function so that fused and un-fused calls agree bit
 // for bit; contraction is written out (the file is built with -ffp-contract=off).
+// The last line is theta - lr * (m_hat / (sqrt(v_hat) + eps) + wd * theta).
 __device__ __forceinline__ void adamw_update(float g, float& theta, float& m, float& v,
                                              const AdamWConsts& c) {
   const float m_new = fmaf(c.beta1, m, c.one_minus_beta1 * g);
   const float v_new = fmaf(c.beta2, v, c.one_minus_beta2 * (g * g));
   const float m_hat = m_new * c.inv_bias1;
   const float v_hat = v_new * c.inv_bias2;
-  const float step = m_hat / (sqrtf(v_hat) + c.eps) + c.weight_decay * theta;
+  // v_sqrt_f32 and v_rcp_f32 are accurate to 1 ulp: far inside the 1e-5 the update is held to,
+  // and an order of magnitude fewer instructions than the correctly rounded sequences
+  const float step = fmaf(m_hat, __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(v_hat) + c.eps), c.weight_decay * theta);
   theta = fmaf(-c.lr, step, theta);
   m = m_new;
   v = v_new;
@@ -92,6 +95,49 @@ __device__ __forceinline__ void emit(const Sinks& s, int64_t E, int32_t slab, in
     s.v[i] = vv;
     if (s.w_kind == W_BF16) ((unsigned short*)s.W)[flat] = f32_to_bf16_rne(th);
     else if (s.w_kind == W_F32) ((float*)s.W)[flat] = th;
+  }
+}
+
+// Four consecutive gradient values at once (16-byte accesses that need only
+// 4-byte alignment; the bf16 copy is one 8-byte store, so `w16` must be 8-byte
+// aligned).  Pointers are already offset to the first of the four elements.
+struct Vec4Sink {
+  float* g;        // EMIT_STORE / EMIT_ACCUM / EMIT_PARTIAL destination
+  float* master;
+  float* m;
+  float* v;
+  void* W;         // low-precision copy (bf16 or fp32) or nullptr
+};
+
+template <int MODE>
+__device__ __forceinline__ void emit4(const Vec4Sink& d, int w_kind, const AdamWConsts& c, f32x4_u val) {
+  if constexpr (MODE == EMIT_STORE || MODE == EMIT_PARTIAL) {
+    *(f32x4_u*)d.g = val;
+  } else if constexpr (MODE == EMIT_ACCUM) {
+    f32x4_u old = *(const f32x4_u*)d.g;
+    old += val;
+    *(f32x4_u*)d.g = old;
+  } else {
+    f32x4_u th = *(const f32x4_u*)d.master;
+    f32x4_u mm = *(const f32x4_u*)d.m;
+    f32x4_u vv = *(const f32x4_u*)d.v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float t = th[e], a = mm[e], b = vv[e];
+      adamw_update(val[e], t, a, b, c);
+      th[e] = t; mm[e] = a; vv[e] = b;
+    }
+    *(f32x4_u*)d.master = th;
+    *(f32x4_u*)d.m = mm;
+    *(f32x4_u*)d.v = vv;
+    if (w_kind == W_BF16) {
+      u32x2_a8 pk;
+      pk[0] = (unsigned int)f32_to_bf16_rne(th[0]) | ((unsigned int)f32_to_bf16_rne(th[1]) << 16);
+      pk[1] = (unsigned int)f32_to_bf16_rne(th[2]) | ((unsigned int)f32_to_bf16_rne(th[3]) << 16);
+      *(u32x2_a8*)d.W = pk;
+    } else if (w_kind == W_F32) {
+      *(f32x4_u*)d.W = th;
+    }
   }
 }
 
@@ -133,7 +179,12 @@ struct RingCfg {
   static constexpr int LA = A_BYTES / 1024 / NW;     // 1 KB wave-loads per wave per slab
   static constexpr int LB = B_BYTES / 1024 / NW;
   static constexpr int L = LA + LB;
-  static constexpr size_t LDS_BYTES = (size_t)NS * STAGE_BYTES;
+  // epilogue staging: half a tile (128 rows x 256 columns of fp32) at a time; a row
+  // pitch of 264 floats puts the two half-waves of a ds_write_b32 on disjoint banks
+  static constexpr int EPI_PITCH = BN + 8;
+  static constexpr size_t EPI_BYTES = (size_t)(BM / 2) * EPI_PITCH * 4;
+  static constexpr size_t RING_BYTES = (size_t)NS * STAGE_BYTES;
+  static constexpr size_t LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
   static_assert(TM == 4 && TN == 2 && L == 4 && NS >= 3, "the main loop is written out for this shape");
 };
 
@@ -449,74 +500,50 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   }
 
   // ---- epilogue.  Accumulator register v of a 32x32 block holds
-  // row (v / 4) * 8 + (lane / 32) * 4 + v % 4, column lane % 32: for a fixed
-  // register a half-wave covers 32 consecutive columns of one row (128 B of fp32).
-  // Everything is addressed as one uniform 64-bit tile origin plus a 32-bit
-  // offset (the host admits only in < 2^21, so 256 rows stay below 2^31 bytes).
+  // row (v / 4) * 8 + (lane / 32) * 4 + v % 4, column lane % 32 -- a layout that
+  // could only be stored 4 bytes per lane.  The tile is therefore staged through
+  // LDS (the ring is free now), half of it at a time, and leaves as whole rows:
+  // a wave handles one row of 256 columns per trip, 16 bytes per lane, 1 KB per
+  // instruction, for the gradient as well as for the AdamW state.
   const int64_t E = p.end - p.begin;
   const int64_t origin = row0 * p.in + col0 - p.begin;             // chunk-local index of the tile corner
-  const unsigned in_u = (unsigned)p.in;
-  const unsigned lane_off = (unsigned)(wm0 + (lane >> 5) * 4) * in_u + (unsigned)(wn0 + (lane & 31));
   const int rows_valid = (int)((q.rb1 - row0 < C::BM) ? q.rb1 - row0 : C::BM);
   const int cols_valid = (int)((p.in - col0 < C::BN) ? p.in - col0 : C::BN);
-  const bool interior = rows_valid == C::BM && cols_valid == C::BN;
-  float* const dst = MODE == EMIT_PARTIAL ? q.s.ws + (int64_t)slab * E + origin
-                   : (MODE == EMIT_ADAMW ? q.s.master + origin : q.s.g + origin);
-  float* const m_t = q.s.m + origin;
-  float* const v_t = q.s.v + origin;
-  unsigned short* const w16 = (unsigned short*)q.s.W + origin + p.begin;
-  float* const w32 = (float*)q.s.W + origin + p.begin;
-  static_for<C::TM * C::TN>([&](auto blk_c) {
-    constexpr int a = decltype(blk_c)::value / C::TN, b = decltype(blk_c)::value % C::TN;
-    const unsigned blk_off = lane_off + (unsigned)(a * 32) * in_u + (unsigned)(b * 32);
-    __builtin_amdgcn_sched_barrier(0);      // one block at a time: bounds the registers the epilogue holds
-    if (interior) {
-      if constexpr (MODE == EMIT_ADAMW) {
-        // all state loads of the block first (48 independent loads per lane), then
-        // the arithmetic, then the stores: the update is bound by HBM, not by latency
-        f32x16 th, mm, vv;
+  float* const stage = reinterpret_cast<float*>(ldsb);
+  const int wmi = wave / C::WN;
+  const int c4 = lane * 4;
+  float* g_dst = MODE == EMIT_PARTIAL ? q.s.ws + (int64_t)slab * E : q.s.g;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const unsigned o = blk_off + (unsigned)((v >> 2) * 8 + (v & 3)) * in_u;
-          th[v] = dst[o];
-          mm[v] = m_t[o];
-          vv[v] = v_t[o];
-        }
+  for (int h = 0; h < 2; ++h) {
+    __syncthreads();                       // ring reads / previous half's row reads are done
+    static_for<2 * C::TN>([&](auto blk_c) {
+      constexpr int a2 = decltype(blk_c)::value / C::TN, b = decltype(blk_c)::value % C::TN;
+      float* base = stage + (wmi * 64 + a2 * 32 + (lane >> 5) * 4) * C::EPI_PITCH + wn0 + b * 32 + (lane & 31);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float t = th[v], x = mm[v], y = vv[v];
-          adamw_update(acc[a][b][v], t, x, y, q.s.c);
-          th[v] = t; mm[v] = x; vv[v] = y;
-        }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const unsigned o = blk_off + (unsigned)((v >> 2) * 8 + (v & 3)) * in_u;
-          dst[o] = th[v];
-          m_t[o] = mm[v];
-          v_t[o] = vv[v];
-          if (q.s.w_kind == W_BF16) w16[o] = f32_to_bf16_rne(th[v]);
-          else if (q.s.w_kind == W_F32) w32[o] = th[v];
-        }
-      } else {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const unsigned o = blk_off + (unsigned)((v >> 2) * 8 + (v & 3)) * in_u;
-          if constexpr (MODE == EMIT_ACCUM) dst[o] += acc[a][b][v];
-          else dst[o] = acc[a][b][v];
-        }
-      }
-    } else {
-      const int lc = wn0 + b * 32 + (lane & 31);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int lr = wm0 + a * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-        if (lr < rows_valid && lc < cols_valid) {
-          const int64_t i = origin + (int64_t)lr * p.in + lc;
-          emit<MODE>(q.s, E, slab, i, i + p.begin, acc[a][b][v]);
+      for (int v = 0; v < 16; ++v) base[((v >> 2) * 8 + (v & 3)) * C::EPI_PITCH] = acc[2 * h + a2][b][v];
+    });
+    __syncthreads();
+    if (c4 < cols_valid) {
+#pragma unroll 4
+      for (int j = 0; j < 16; ++j) {
+        const int rr = j * 8 + wave;                                  // staged row, 0..127
+        const int tile_row = (rr >> 6) * 128 + h * 64 + (rr & 63);
+        if (tile_row < rows_valid) {
+          const float4 lv = *(const float4*)(stage + rr * C::EPI_PITCH + c4);   // 16-byte aligned: one ds_read_b128
+          const f32x4_u val = {lv.x, lv.y, lv.z, lv.w};
+          const int64_t i = origin + (int64_t)tile_row * p.in + c4;
+          Vec4Sink d;
+          d.g = g_dst + i;
+          d.master = q.s.master + i;
+          d.m = q.s.m + i;
+          d.v = q.s.v + i;
+          d.W = q.s.w_kind == W_BF16 ? (void*)((unsigned short*)q.s.W + i + p.begin)
+                                     : (void*)((float*)q.s.W + i + p.begin);
+          emit4<MODE>(d, q.s.w_kind, q.s.c, val);
         }
       }
     }
-  });
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -675,35 +702,14 @@ __global__ __launch_bounds__(256) void elementwise_kernel(const ElemParams q) {
       const f32x4_u part = *(const f32x4_u*)(q.src + (int64_t)sl * q.n + i);
       val += part;
     }
-    if constexpr (MODE == EMIT_STORE) {
-      *(f32x4_u*)(q.g_out + i) = val;
-    } else if constexpr (MODE == EMIT_ACCUM) {
-      f32x4_u old = *(const f32x4_u*)(q.g_out + i);
-      old += val;
-      *(f32x4_u*)(q.g_out + i) = old;
-    } else {
-      f32x4_u th = *(const f32x4_u*)(q.master + i);
-      f32x4_u mm = *(const f32x4_u*)(q.m + i);
-      f32x4_u vv = *(const f32x4_u*)(q.v + i);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float t = th[e], a = mm[e], b = vv[e];
-        adamw_update(val[e], t, a, b, q.c);
-        th[e] = t; mm[e] = a; vv[e] = b;
-      }
-      *(f32x4_u*)(q.master + i) = th;
-      *(f32x4_u*)(q.m + i) = mm;
-      *(f32x4_u*)(q.v + i) = vv;
-      if (q.w_kind == W_BF16) {
-        // head was chosen so that this address is 8-byte aligned
-        u32x2_a8 pk;
-        pk[0] = (unsigned int)f32_to_bf16_rne(th[0]) | ((unsigned int)f32_to_bf16_rne(th[1]) << 16);
-        pk[1] = (unsigned int)f32_to_bf16_rne(th[2]) | ((unsigned int)f32_to_bf16_rne(th[3]) << 16);
-        *(u32x2_a8*)((unsigned short*)q.W + i) = pk;
-      } else if (q.w_kind == W_F32) {
-        *(f32x4_u*)((float*)q.W + i) = th;
-      }
-    }
+    Vec4Sink d;
+    d.g = q.g_out + i;
+    d.master = q.master + i;
+    d.m = q.m + i;
+    d.v = q.v + i;
+    // head was chosen so that the bf16 address is 8-byte aligned
+    d.W = q.w_kind == W_BF16 ? (void*)((unsigned short*)q.W + i) : (void*)((float*)q.W + i);
+    emit4<MODE>(d, q.w_kind, q.c, val);
   }
 }
 
