@@ -27,7 +27,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef float f32x4_u __attribute__((ext_vector_type(4), aligned(4)));   // 16 bytes at any dword
-typedef unsigned int u32x2_a8 __attribute__((ext_vector_type(2), aligned(8)));
+typedef unsigned int u32x2_a2 __attribute__((ext_vector_type(2), aligned(2)));   // 8 bytes at any bf16
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 
 // Compile-time loop: the body sees its index as a constant, so register arrays
@@ -98,9 +98,11 @@ __device__ __forceinline__ void emit(const Sinks& s, int64_t E, int32_t slab, in
   }
 }
 
-// Four consecutive gradient values at once (16-byte accesses that need only
-// 4-byte alignment; the bf16 copy is one 8-byte store, so `w16` must be 8-byte
-// aligned).  Pointers are already offset to the first of the four elements.
+// Four consecutive gradient values at once.  The 16-byte fp32 accesses work at
+// any 4-byte alignment but stream about 15% faster when 16-byte aligned, whereas
+// the 8-byte bf16 store costs next to nothing at 2-byte alignment: callers align
+// their groups of four to the fp32 arrays.  Pointers are already offset to the
+// first of the four elements.
 struct Vec4Sink {
   float* g;        // EMIT_STORE / EMIT_ACCUM / EMIT_PARTIAL destination
   float* master;
@@ -109,34 +111,51 @@ struct Vec4Sink {
   void* W;         // low-precision copy (bf16 or fp32) or nullptr
 };
 
+// Chunk state and gradients are streamed: read once, written once, never reused
+// by the same kernel, and far larger than the caches.  All these accesses carry
+// the non-temporal hint.
+struct State4 {
+  f32x4_u th, mm, vv;
+};
+
 template <int MODE>
-__device__ __forceinline__ void emit4(const Vec4Sink& d, int w_kind, const AdamWConsts& c, f32x4_u val) {
+__device__ __forceinline__ State4 load_state4(const Vec4Sink& d) {
+  State4 st;
+  if constexpr (MODE == EMIT_ACCUM) {
+    st.th = __builtin_nontemporal_load((const f32x4_u*)d.g);
+  } else if constexpr (MODE == EMIT_ADAMW) {
+    st.th = __builtin_nontemporal_load((const f32x4_u*)d.master);
+    st.mm = __builtin_nontemporal_load((const f32x4_u*)d.m);
+    st.vv = __builtin_nontemporal_load((const f32x4_u*)d.v);
+  }
+  return st;
+}
+
+template <int MODE>
+__device__ __forceinline__ void finish4(const Vec4Sink& d, int w_kind, const AdamWConsts& c, f32x4_u val,
+                                        State4 st) {
   if constexpr (MODE == EMIT_STORE || MODE == EMIT_PARTIAL) {
-    *(f32x4_u*)d.g = val;
+    __builtin_nontemporal_store(val, (f32x4_u*)d.g);
   } else if constexpr (MODE == EMIT_ACCUM) {
-    f32x4_u old = *(const f32x4_u*)d.g;
-    old += val;
-    *(f32x4_u*)d.g = old;
+    st.th += val;
+    __builtin_nontemporal_store(st.th, (f32x4_u*)d.g);
   } else {
-    f32x4_u th = *(const f32x4_u*)d.master;
-    f32x4_u mm = *(const f32x4_u*)d.m;
-    f32x4_u vv = *(const f32x4_u*)d.v;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      float t = th[e], a = mm[e], b = vv[e];
+      float t = st.th[e], a = st.mm[e], b = st.vv[e];
       adamw_update(val[e], t, a, b, c);
-      th[e] = t; mm[e] = a; vv[e] = b;
+      st.th[e] = t; st.mm[e] = a; st.vv[e] = b;
     }
-    *(f32x4_u*)d.master = th;
-    *(f32x4_u*)d.m = mm;
-    *(f32x4_u*)d.v = vv;
+    __builtin_nontemporal_store(st.th, (f32x4_u*)d.master);
+    __builtin_nontemporal_store(st.mm, (f32x4_u*)d.m);
+    __builtin_nontemporal_store(st.vv, (f32x4_u*)d.v);
     if (w_kind == W_BF16) {
-      u32x2_a8 pk;
-      pk[0] = (unsigned int)f32_to_bf16_rne(th[0]) | ((unsigned int)f32_to_bf16_rne(th[1]) << 16);
-      pk[1] = (unsigned int)f32_to_bf16_rne(th[2]) | ((unsigned int)f32_to_bf16_rne(th[3]) << 16);
-      *(u32x2_a8*)d.W = pk;
+      u32x2_a2 pk;
+      pk[0] = (unsigned int)f32_to_bf16_rne(st.th[0]) | ((unsigned int)f32_to_bf16_rne(st.th[1]) << 16);
+      pk[1] = (unsigned int)f32_to_bf16_rne(st.th[2]) | ((unsigned int)f32_to_bf16_rne(st.th[3]) << 16);
+      __builtin_nontemporal_store(pk, (u32x2_a2*)d.W);
     } else if (w_kind == W_F32) {
-      *(f32x4_u*)d.W = th;
+      __builtin_nontemporal_store(st.th, (f32x4_u*)d.W);
     }
   }
 }
@@ -511,8 +530,25 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   const int cols_valid = (int)((p.in - col0 < C::BN) ? p.in - col0 : C::BN);
   float* const stage = reinterpret_cast<float*>(ldsb);
   const int wmi = wave / C::WN;
-  const int c4 = lane * 4;
-  float* g_dst = MODE == EMIT_PARTIAL ? q.s.ws + (int64_t)slab * E : q.s.g;
+  float* const g_dst = MODE == EMIT_PARTIAL ? q.s.ws + (int64_t)slab * E : q.s.g;
+  // Groups of four columns start where the fp32 destination is 16-byte aligned:
+  // at tile-local column delta (the same for every row, because in % 8 == 0).
+  // The delta leading and 4 - delta trailing columns of a row that are left over
+  // are taken one element per thread (128 rows x 4 = 512 of them per half tile).
+  const float* const align_ref = MODE == EMIT_ADAMW ? q.s.master : g_dst;
+  const int delta = (int)((4 - ((reinterpret_cast<uintptr_t>(align_ref) >> 2) + (uint64_t)origin) % 4) % 4);
+  const int c4 = delta + lane * 4;
+  const bool vec_lane = delta == 0 || lane < 63;
+  auto sink_at = [&](int64_t i) {
+    Vec4Sink d;
+    d.g = g_dst + i;
+    d.master = q.s.master + i;
+    d.m = q.s.m + i;
+    d.v = q.s.v + i;
+    d.W = q.s.w_kind == W_BF16 ? (void*)((unsigned short*)q.s.W + i + p.begin)
+                               : (void*)((float*)q.s.W + i + p.begin);
+    return d;
+  };
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     __syncthreads();                       // ring reads / previous half's row reads are done
@@ -523,24 +559,37 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
       for (int v = 0; v < 16; ++v) base[((v >> 2) * 8 + (v & 3)) * C::EPI_PITCH] = acc[2 * h + a2][b][v];
     });
     __syncthreads();
-    if (c4 < cols_valid) {
-#pragma unroll 4
-      for (int j = 0; j < 16; ++j) {
-        const int rr = j * 8 + wave;                                  // staged row, 0..127
-        const int tile_row = (rr >> 6) * 128 + h * 64 + (rr & 63);
-        if (tile_row < rows_valid) {
-          const float4 lv = *(const float4*)(stage + rr * C::EPI_PITCH + c4);   // 16-byte aligned: one ds_read_b128
-          const f32x4_u val = {lv.x, lv.y, lv.z, lv.w};
-          const int64_t i = origin + (int64_t)tile_row * p.in + c4;
-          Vec4Sink d;
-          d.g = g_dst + i;
-          d.master = q.s.master + i;
-          d.m = q.s.m + i;
-          d.v = q.s.v + i;
-          d.W = q.s.w_kind == W_BF16 ? (void*)((unsigned short*)q.s.W + i + p.begin)
-                                     : (void*)((float*)q.s.W + i + p.begin);
-          emit4<MODE>(d, q.s.w_kind, q.s.c, val);
+    if (vec_lane && c4 + 4 <= cols_valid) {
+      // four rows per trip: their state loads are issued together, then the updates
+      for (int j0 = 0; j0 < 16; j0 += 4) {
+        Vec4Sink d[4];
+        State4 st[4];
+        bool ok[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int rr = (j0 + u) * 8 + wave;                            // staged row, 0..127
+          const int tile_row = (rr >> 6) * 128 + h * 64 + (rr & 63);
+          ok[u] = tile_row < rows_valid;
+          d[u] = sink_at(origin + (int64_t)tile_row * p.in + c4);
+          if (ok[u]) st[u] = load_state4<MODE>(d[u]);
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (ok[u]) {
+            const float* src = stage + ((j0 + u) * 8 + wave) * C::EPI_PITCH + c4;
+            const f32x4_u val = {src[0], src[1], src[2], src[3]};
+            finish4<MODE>(d[u], q.s.w_kind, q.s.c, val, st[u]);
+          }
+        }
+      }
+    }
+    if (delta != 0) {
+      const int rr = tid >> 2, e = tid & 3;
+      const int tile_row = (rr >> 6) * 128 + h * 64 + (rr & 63);
+      const int lc = e < delta ? e : cols_valid - 4 + e;      // cols_valid is a multiple of 8
+      if (tile_row < rows_valid) {
+        const int64_t i = origin + (int64_t)tile_row * p.in + lc;
+        emit<MODE>(q.s, E, slab, i, i + p.begin, stage[rr * C::EPI_PITCH + lc]);
       }
     }
   }
@@ -695,21 +744,32 @@ __global__ __launch_bounds__(256) void elementwise_kernel(const ElemParams q) {
     if (ok) elem_one<MODE>(q, i);
   }
   const int64_t stride = (int64_t)gridDim.x * 256;
-  for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < nvec; j += stride) {
-    const int64_t i = q.head + (j << 2);
-    f32x4_u val = *(const f32x4_u*)(q.src + i);
-    for (int32_t sl = 1; sl < q.S; ++sl) {
-      const f32x4_u part = *(const f32x4_u*)(q.src + (int64_t)sl * q.n + i);
-      val += part;
+  // two 4-element groups per trip, all loads ahead of the arithmetic
+  for (int64_t j0 = (int64_t)blockIdx.x * 256 + threadIdx.x; j0 < nvec; j0 += 2 * stride) {
+    Vec4Sink d[2];
+    State4 st[2];
+    f32x4_u val[2];
+    bool ok[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int64_t j = j0 + u * stride;
+      ok[u] = j < nvec;
+      const int64_t i = q.head + (j << 2);
+      d[u].g = q.g_out + i;
+      d[u].master = q.master + i;
+      d[u].m = q.m + i;
+      d[u].v = q.v + i;
+      d[u].W = q.w_kind == W_BF16 ? (void*)((unsigned short*)q.W + i) : (void*)((float*)q.W + i);
+      if (ok[u]) {
+        val[u] = __builtin_nontemporal_load((const f32x4_u*)(q.src + i));
+        for (int32_t sl = 1; sl < q.S; ++sl)
+          val[u] += __builtin_nontemporal_load((const f32x4_u*)(q.src + (int64_t)sl * q.n + i));
+        st[u] = load_state4<MODE>(d[u]);
+      }
     }
-    Vec4Sink d;
-    d.g = q.g_out + i;
-    d.master = q.master + i;
-    d.m = q.m + i;
-    d.v = q.v + i;
-    // head was chosen so that the bf16 address is 8-byte aligned
-    d.W = q.w_kind == W_BF16 ? (void*)((unsigned short*)q.W + i) : (void*)((float*)q.W + i);
-    emit4<MODE>(d, q.w_kind, q.c, val);
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      if (ok[u]) finish4<MODE>(d[u], q.w_kind, q.c, val[u], st[u]);
   }
 }
 
@@ -885,20 +945,15 @@ int launch_colsum(const WgradProblem& p, int dtype, int mode, const Sinks& s, vo
 }
 
 static int launch_elem(ElemParams& q, int mode, hipStream_t st) {
-  // the first 4-element group starts where the low-precision store is 8-byte
-  // aligned (bf16), else where the fp32 state is 16-byte aligned
-  int64_t head;
-  if (q.w_kind == W_BF16 && mode == EMIT_ADAMW)
-    head = ((8 - (reinterpret_cast<uintptr_t>(q.W) & 7u)) & 7u) / 2;
-  else {
-    const void* ref = mode == EMIT_ADAMW ? (const void*)q.master : (const void*)q.g_out;
-    head = ((16 - (reinterpret_cast<uintptr_t>(ref) & 15u)) & 15u) / 4;
-  }
+  // the first 4-element group starts where the fp32 arrays are 16-byte aligned
+  // (judged by the master weights for the update, by the output gradient otherwise)
+  const void* ref = mode == EMIT_ADAMW ? (const void*)q.master : (const void*)q.g_out;
+  int64_t head = ((16 - (reinterpret_cast<uintptr_t>(ref) & 15u)) & 15u) / 4;
   if (head > q.n) head = q.n;
   q.head = head;
   const int64_t nvec = (q.n - head) >> 2;
-  int64_t blocks = ceil_div(nvec, 256);
-  const int64_t cap = (int64_t)kNumCU * 16;
+  int64_t blocks = ceil_div(nvec, 512);
+  const int64_t cap = (int64_t)kNumCU * 2;        // two resident blocks per CU stream best
   if (blocks > cap) blocks = cap;
   if (blocks < 1) blocks = 1;
   switch (mode) {
