@@ -135,10 +135,12 @@ template <int MODE>
 __device__ __forceinline__ void finish4(const Vec4Sink& d, int w_kind, const AdamWConsts& c, f32x4_u val,
                                         State4 st) {
   if constexpr (MODE == EMIT_STORE || MODE == EMIT_PARTIAL) {
-    __builtin_nontemporal_store(val, (f32x4_u*)d.g);
+    // the gradient is read again by the next kernel (AdamW or the slab reduction):
+    // a plain store lets the 256 MB memory-side cache keep it
+    *(f32x4_u*)d.g = val;
   } else if constexpr (MODE == EMIT_ACCUM) {
     st.th += val;
-    __builtin_nontemporal_store(st.th, (f32x4_u*)d.g);
+    *(f32x4_u*)d.g = st.th;
   } else {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -310,9 +312,9 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // to the GLOBAL address each lane fetches, LDS writes stay linear.
 //
 // Schedule.  Per 32-token slab a wave issues 16 MFMAs in two 16-token steps.
-// After every pair of MFMAs it issues three transpose reads for the NEXT step
-// and, in the first step, one global->LDS load of a later slab, so LDS, the
-// vector-memory pipe and the matrix pipe are all fed evenly instead of in bursts.
+// The transpose reads of the NEXT step are issued behind the first three MFMAs
+// of a step and the global->LDS loads of a later slab behind the following four,
+// so their latency runs under the remaining MFMAs instead of in front of a wait.
 // One s_barrier per slab: it publishes slab kt+1 (every wave waited for its own
 // loads of it) and retires slab kt-1, whose buffer the new loads overwrite.
 template <class C, int MODE>
@@ -385,10 +387,13 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   }
   const int64_t stepA = (int64_t)C::BK * p.lddy, stepB = (int64_t)C::BK * p.ldx;
   int next_fetch = 0;   // slab index the pointers stand at
-  auto issue_one = [&](auto idxc) {
-    constexpr int idx = decltype(idxc)::value;
-    const int stage = next_fetch % C::NS;
-    const bool ragged = (next_fetch + 1) * C::BK > klen;     // only the last slab can be
+  // One of the L loads of slab `next_fetch`.  STAGE >= 0: the steady-state form, ring
+  // slot known at compile time and the slab known to be complete; STAGE < 0: the general
+  // form for the first and last slabs.
+  auto issue_one = [&](auto idxc, auto stagec) {
+    constexpr int idx = decltype(idxc)::value, STAGE = decltype(stagec)::value;
+    const int stage = STAGE >= 0 ? STAGE : next_fetch % C::NS;
+    const bool ragged = STAGE >= 0 ? false : (next_fetch + 1) * C::BK > klen;     // only the last slab can be
     if constexpr (idx < C::LA) {
       constexpr int i = idx;
       const unsigned short* src = pa[i];
@@ -424,13 +429,19 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   const int swl = (i16 >> 2) | ((blk >> 1) << 2);
   const int low = (blk & 1) * 2 + ((i16 & 3) >> 1);     // low two bits of the 16-byte slot index
   const int sub = (i16 & 1) * 8;                        // byte offset inside the slot
-  unsigned addrA[C::TM], addrB[C::TN];
+  // Two bases 64 KB apart per block: with the ring slot known at compile time every
+  // read then has an immediate offset (the field holds 16 bits) and costs no VALU add.
+  unsigned addrA[C::TM], addrB[C::TN], addrA_hi[C::TM], addrB_hi[C::TN];
 #pragma unroll
-  for (int a = 0; a < C::TM; ++a)
+  for (int a = 0; a < C::TM; ++a) {
     addrA[a] = lds_base + tr_k * 512 + ((((wm0 >> 3) + a * 4) ^ (swl << 2)) + low) * 16 + sub;
+    addrA_hi[a] = addrA[a] + 65536;
+  }
 #pragma unroll
-  for (int b = 0; b < C::TN; ++b)
+  for (int b = 0; b < C::TN; ++b) {
     addrB[b] = lds_base + C::A_BYTES + tr_k * 512 + ((((wn0 >> 3) + b * 4) ^ (swl << 2)) + low) * 16 + sub;
+    addrB_hi[b] = addrB[b] + 65536;
+  }
 
   // Fragment halves: unit u < 8 is A block u/2 (tokens 0-3 | 8-11 if u is even,
   // 4-7 | 12-15 if odd), unit u >= 8 is B block (u-8)/2 likewise.
@@ -440,6 +451,14 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
     constexpr int off = (ks * 16 + (u & 1) * 4) * 512;
     if constexpr (u < 8) h[u] = lds_tr_read<off>(addrA[u / 2] + so);
     else h[u] = lds_tr_read<off>(addrB[(u - 8) / 2] + so);
+  };
+  auto read_unit_at = [&](bf16x4* h, auto stagec, auto ksc, auto uc) {      // ring slot at compile time
+    constexpr int st = decltype(stagec)::value, ks = decltype(ksc)::value, u = decltype(uc)::value;
+    constexpr int so = st * C::STAGE_BYTES;
+    constexpr int off = (so & 0xFFFF) + (ks * 16 + (u & 1) * 4) * 512;
+    static_assert(off < 65536, "LDS offset field");
+    if constexpr (u < 8) h[u] = lds_tr_read<off>(so < 65536 ? addrA[u / 2] : addrA_hi[u / 2]);
+    else h[u] = lds_tr_read<off>(so < 65536 ? addrB[(u - 8) / 2] : addrB_hi[(u - 8) / 2]);
   };
   auto frag = [&](const bf16x4* h, int u) {
     return __builtin_shufflevector(h[u], h[u + 1], 0, 1, 2, 3, 4, 5, 6, 7);
@@ -467,7 +486,7 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
 #pragma unroll
   for (int s = 0; s < C::NS - 1; ++s)
     if (s < nk) {
-      static_for<C::L>([&](auto ic) { issue_one(ic); });
+      static_for<C::L>([&](auto ic) { issue_one(ic, IntC<-1>{}); });
       ++next_fetch;
     }
   if (C::NS - 2 < nk) wait_vmcnt<(C::NS - 2) * C::L>(); else wait_vmcnt<0>();
@@ -476,47 +495,71 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   WAIT_HALVES(h0);
   mask_halves(h0, 0, 0);
 
-  for (int kt = 0; kt < nk; ++kt) {
+  // One slab: sixteen MFMAs in two steps of eight, numbered i = 2a + b within a
+  // step.  The twelve transpose reads of the next step follow MFMAs 0-2 (four
+  // each), so the last of them has five MFMAs of time to return; the four
+  // global->LDS loads follow MFMAs 3-6 of the first step.  KM >= 0 is the
+  // steady-state form (kt mod NS known at compile time, a later slab always
+  // fetched, nothing ragged): no branch, no address arithmetic.  KM < 0 is the
+  // general form used for the last slabs.
+  auto do_slab = [&](int kt, auto kmc) {
+    constexpr int KM = decltype(kmc)::value;
+    constexpr bool FAST = KM >= 0;
     // slab kt+1 has landed once at most the NS-3 younger slabs are outstanding
-    if (kt + C::NS - 2 < nk) wait_vmcnt<(C::NS - 3) * C::L>(); else wait_vmcnt<0>();
+    if (FAST || kt + C::NS - 2 < nk) wait_vmcnt<(C::NS - 3) * C::L>(); else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
-    const bool fetch = kt + C::NS - 1 < nk;
-    const bool more = kt + 1 < nk;
+    const bool fetch = FAST || kt + C::NS - 1 < nk;
+    const bool more = FAST || kt + 1 < nk;
     const unsigned so = (unsigned)((kt % C::NS) * C::STAGE_BYTES);
     const unsigned so_next = (unsigned)(((kt + 1) % C::NS) * C::STAGE_BYTES);
-    static_for<4>([&](auto ac) {
-      constexpr int a = decltype(ac)::value;
+    static_for<8>([&](auto ic) {
+      constexpr int i = decltype(ic)::value, a = i / 2, b = i % 2;
       __builtin_amdgcn_sched_barrier(0);
-      acc[a][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h0, 2 * a), frag(h0, 8), acc[a][0], 0, 0, 0);
-      acc[a][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h0, 2 * a), frag(h0, 10), acc[a][1], 0, 0, 0);
+      acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h0, 2 * a), frag(h0, 8 + 2 * b), acc[a][b], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      read_unit(h1, so, IntC<1>{}, IntC<3 * a>{});
-      read_unit(h1, so, IntC<1>{}, IntC<3 * a + 1>{});
-      read_unit(h1, so, IntC<1>{}, IntC<3 * a + 2>{});
-      if (fetch) issue_one(ac);
+      if constexpr (i < 3) {
+        static_for<4>([&](auto jc) {
+          constexpr int u = 4 * i + decltype(jc)::value;
+          if constexpr (FAST) read_unit_at(h1, IntC<(KM >= 0 ? KM : 0)>{}, IntC<1>{}, IntC<u>{});
+          else read_unit(h1, so, IntC<1>{}, IntC<u>{});
+        });
+      } else if constexpr (i < 7) {
+        if constexpr (FAST) issue_one(IntC<i - 3>{}, IntC<(KM >= 0 ? (KM + C::NS - 1) % C::NS : 0)>{});
+        else if (fetch) issue_one(IntC<i - 3>{}, IntC<-1>{});
+      }
     });
     if (fetch) ++next_fetch;
     __builtin_amdgcn_sched_barrier(0);
     WAIT_HALVES(h1);
-    mask_halves(h1, kt, 1);
-    static_for<4>([&](auto ac) {
-      constexpr int a = decltype(ac)::value;
+    if constexpr (!FAST) mask_halves(h1, kt, 1);
+    static_for<8>([&](auto ic) {
+      constexpr int i = decltype(ic)::value, a = i / 2, b = i % 2;
       __builtin_amdgcn_sched_barrier(0);
-      acc[a][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h1, 2 * a), frag(h1, 8), acc[a][0], 0, 0, 0);
-      acc[a][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h1, 2 * a), frag(h1, 10), acc[a][1], 0, 0, 0);
+      acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h1, 2 * a), frag(h1, 8 + 2 * b), acc[a][b], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      if (more) {
-        read_unit(h0, so_next, IntC<0>{}, IntC<3 * a>{});
-        read_unit(h0, so_next, IntC<0>{}, IntC<3 * a + 1>{});
-        read_unit(h0, so_next, IntC<0>{}, IntC<3 * a + 2>{});
+      if constexpr (i < 3) {
+        static_for<4>([&](auto jc) {
+          constexpr int u = 4 * i + decltype(jc)::value;
+          if constexpr (FAST) read_unit_at(h0, IntC<(KM >= 0 ? (KM + 1) % C::NS : 0)>{}, IntC<0>{}, IntC<u>{});
+          else if (more) read_unit(h0, so_next, IntC<0>{}, IntC<u>{});
+        });
       }
     });
     __builtin_amdgcn_sched_barrier(0);
     if (more) {
       WAIT_HALVES(h0);
-      mask_halves(h0, kt + 1, 0);
+      if constexpr (!FAST) mask_halves(h0, kt + 1, 0);
     }
-  }
+  };
+
+  // Steady state: slabs whose fetch (of slab kt + NS - 1) exists and is complete, in
+  // groups of NS so that the ring slot is a compile-time constant.
+  const bool last_ragged = (klen % C::BK) != 0;
+  const int n_fast = (nk - (C::NS - 1) - (last_ragged ? 1 : 0)) / C::NS * C::NS;
+  int kt = 0;
+  for (; kt < n_fast; kt += C::NS)
+    static_for<C::NS>([&](auto kmc) { do_slab(kt + decltype(kmc)::value, kmc); });
+  for (; kt < nk; ++kt) do_slab(kt, IntC<-1>{});
 
   // ---- epilogue.  Accumulator register v of a 32x32 block holds
   // row (v / 4) * 8 + (lane / 32) * 4 + v % 4, column lane % 32 -- a layout that
