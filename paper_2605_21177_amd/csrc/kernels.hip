@@ -215,9 +215,9 @@ struct RingCfg {
 // loads of kEdgeUnroll tokens are issued together, so a trip costs one memory
 // latency.  The 32 token-group partials meet in LDS and are added in group order.
 constexpr int kEdgeCols = 32;
-constexpr int kEdgeTG = 32;
+constexpr int kEdgeTG = 16;
 constexpr int kEdgeThreads = kEdgeCols * kEdgeTG;
-constexpr int kEdgeUnroll = 8;
+constexpr int kEdgeUnroll = 32;
 
 template <int MODE>
 __global__ __launch_bounds__(kEdgeThreads) void wgrad_edge_kernel(const EdgeParams q) {
