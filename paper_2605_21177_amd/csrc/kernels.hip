@@ -169,14 +169,18 @@ __device__ __forceinline__ void finish4(const Vec4Sink& d, int w_kind, const Ada
 //   body rows [rb0, rb1): complete rows, rb0 a multiple of 8 (16-byte dY loads),
 //   computed by the MFMA kernel with no range mask beyond the row bound;
 //   edge rows: the partial first row, the up-to-7 complete rows before rb0, and
-//   the partial last row -- at most kMaxEdgeRows of them, computed by the FMA
-//   edge kernel that runs ahead of the MFMA kernel on the same stream.
+//   the partial last row -- at most kMaxEdgeRows of them.  The workgroups of the
+//   first tile row, which stream every X column tile anyway, carry them as one
+//   extra 32-row MFMA block; only when there is no body at all (a chunk of a few
+//   rows) does the small FMA edge kernel compute them.
 struct MfmaParams {
   WgradProblem p;
   int64_t rb0, rb1;
   int32_t tiles_m, tiles_n;
   int32_t n_tile_items;        // tiles_m * tiles_n * S
   int32_t group_m;
+  int64_t lead_base;           // edge rows folded into the first tile row (-1: none), as in EdgeParams
+  int64_t trail_row;
   Sinks s;
 };
 
@@ -196,7 +200,10 @@ struct RingCfg {
   static constexpr int NW = WM * WN, NT = 64 * NW;
   static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   static constexpr int A_BYTES = BK * BM * 2, B_BYTES = BK * BN * 2;
-  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  // edge block: per token 16 row values = the 8-row group of the leading edge rows and
+  // the 8-row group that holds the trailing row (32 B per token, 1 KB per slab)
+  static constexpr int E_BYTES = BK * 32;
+  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES + E_BYTES;
   static constexpr int LA = A_BYTES / 1024 / NW;     // 1 KB wave-loads per wave per slab
   static constexpr int LB = B_BYTES / 1024 / NW;
   static constexpr int L = LA + LB;
@@ -298,6 +305,11 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
                : "+v"(h[0]), "+v"(h[1]), "+v"(h[2]), "+v"(h[3]), "+v"(h[4]), "+v"(h[5]), "+v"(h[6]),     \
                  "+v"(h[7]), "+v"(h[8]), "+v"(h[9]), "+v"(h[10]), "+v"(h[11])::"memory")
 
+#define WAIT_HALVES_E(h, he)                                                                             \
+  asm volatile("s_waitcnt lgkmcnt(0)"                                                                    \
+               : "+v"(h[0]), "+v"(h[1]), "+v"(h[2]), "+v"(h[3]), "+v"(h[4]), "+v"(h[5]), "+v"(h[6]),     \
+                 "+v"(h[7]), "+v"(h[8]), "+v"(h[9]), "+v"(h[10]), "+v"(h[11]), "+v"(he[0]), "+v"(he[1])::"memory")
+
 // One 256 x 256 tile of body rows over one slab of tokens.
 //
 // Data movement.  dY and X are [token][row] / [token][column]: both operands have
@@ -387,6 +399,34 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   }
   const int64_t stepA = (int64_t)C::BK * p.lddy, stepB = (int64_t)C::BK * p.ldx;
   int next_fetch = 0;   // slab index the pointers stand at
+
+  // ---- edge block (first tile row only).  One extra wave-load per slab, issued by
+  // wave 0: lane l fetches, for token l/2, the 8-row group of the leading edge rows
+  // (l even) or the one holding the trailing row (l odd); a missing group is
+  // replaced by the tile's first rows (valid memory, masked in the epilogue).
+  const bool has_edge = tile_m == 0 && (q.lead_base >= 0 || q.trail_row >= 0);
+  const int ke = lane >> 1;
+  const unsigned short* ge;
+  {
+    const int64_t lead = q.lead_base >= 0 ? q.lead_base : row0;
+    const int64_t trail = q.trail_row >= 0 ? (q.trail_row & ~(int64_t)7) : row0;
+    ge = dY + ((lane & 1) ? trail : lead);
+  }
+  const unsigned short* pe = ge + (k_begin + ke) * p.lddy;
+  auto issue_edge = [&](auto stagec) {
+    constexpr int STAGE = decltype(stagec)::value;
+    const int stage = STAGE >= 0 ? STAGE : next_fetch % C::NS;
+    const bool ragged = STAGE >= 0 ? false : (next_fetch + 1) * C::BK > klen;
+    const unsigned short* src = pe;
+    if (ragged) {
+      int64_t t = k_begin + (int64_t)next_fetch * C::BK + ke;
+      if (t > p.T - 1) t = p.T - 1;
+      src = ge + t * p.lddy;
+    }
+    const unsigned dst = lds_base + stage * C::STAGE_BYTES + C::A_BYTES + C::B_BYTES;
+    __builtin_amdgcn_global_load_lds((GLB_PTR(const void))src, (LDS_PTR(void))(uintptr_t)dst, 16, 0, 0);
+    pe += stepA;
+  };
   // One of the L loads of slab `next_fetch`.  STAGE >= 0: the steady-state form, ring
   // slot known at compile time and the slab known to be complete; STAGE < 0: the general
   // form for the first and last slabs.
@@ -443,6 +483,34 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
     addrB_hi[b] = addrB[b] + 65536;
   }
 
+  // Edge block reads: token t of a slab sits at byte 32 t, its 16 row values behind it.
+  // Lanes 16-31 and 48-63 (MFMA rows 16-31) re-read rows 0-15; those output rows are dropped.
+  const unsigned addrE = lds_base + C::A_BYTES + C::B_BYTES + tr_k * 32 + (i16 & 3) * 8;
+  const unsigned addrE_hi = addrE + 65536;
+  bf16x4 he0[2], he1[2];
+  f32x16 acc_e;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc_e[v] = 0.f;
+  auto read_edge = [&](bf16x4* he, unsigned so, auto ksc) {
+    constexpr int ks = decltype(ksc)::value;
+    he[0] = lds_tr_read<ks * 16 * 32>(addrE + so);
+    he[1] = lds_tr_read<(ks * 16 + 4) * 32>(addrE + so);
+  };
+  auto read_edge_at = [&](bf16x4* he, auto stagec, auto ksc) {
+    constexpr int st = decltype(stagec)::value, ks = decltype(ksc)::value;
+    constexpr int so = st * C::STAGE_BYTES;
+    constexpr int off = (so & 0xFFFF) + ks * 16 * 32;
+    static_assert(off + 4 * 32 < 65536, "LDS offset field");
+    he[0] = lds_tr_read<off>(so < 65536 ? addrE : addrE_hi);
+    he[1] = lds_tr_read<off + 4 * 32>(so < 65536 ? addrE : addrE_hi);
+  };
+  // the edge MFMA of a wave uses its B block wave / 4: waves w and w + 4 share their 64 columns
+  auto edge_mma = [&](const bf16x4* he, const bf16x4* h) {
+    const bf16x8 fe = __builtin_shufflevector(he[0], he[1], 0, 1, 2, 3, 4, 5, 6, 7);
+    if (wave < 4) acc_e = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fe, __builtin_shufflevector(h[8], h[9], 0, 1, 2, 3, 4, 5, 6, 7), acc_e, 0, 0, 0);
+    else acc_e = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fe, __builtin_shufflevector(h[10], h[11], 0, 1, 2, 3, 4, 5, 6, 7), acc_e, 0, 0, 0);
+  };
+
   // Fragment halves: unit u < 8 is A block u/2 (tokens 0-3 | 8-11 if u is even,
   // 4-7 | 12-15 if odd), unit u >= 8 is B block (u-8)/2 likewise.
   bf16x4 h0[12], h1[12];
@@ -463,7 +531,7 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   auto frag = [&](const bf16x4* h, int u) {
     return __builtin_shufflevector(h[u], h[u + 1], 0, 1, 2, 3, 4, 5, 6, 7);
   };
-  auto mask_halves = [&](bf16x4* h, int kt, int ks) {
+  auto mask_halves = [&](bf16x4* h, bf16x4* he, int kt, int ks) {
     if (kt == nk - 1 && (klen % C::BK) != 0) {
       const int kv = klen - kt * C::BK - ks * 16 - (lane >> 5) * 8;   // valid tokens among this lane's 8
 #pragma unroll
@@ -471,6 +539,11 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
           if ((u & 1) * 4 + e >= kv) h[u][e] = (__bf16)0.f;
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (u * 4 + e >= kv) he[u][e] = (__bf16)0.f;
     }
   };
 
@@ -487,13 +560,22 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   for (int s = 0; s < C::NS - 1; ++s)
     if (s < nk) {
       static_for<C::L>([&](auto ic) { issue_one(ic, IntC<-1>{}); });
+      if (has_edge && wave == 0) issue_edge(IntC<-1>{});
       ++next_fetch;
     }
-  if (C::NS - 2 < nk) wait_vmcnt<(C::NS - 2) * C::L>(); else wait_vmcnt<0>();
+  // wave 0 of an edge workgroup has one more load per slab in flight than the others
+  const bool five = has_edge && wave == 0;
+  if (C::NS - 2 < nk) {
+    if (five) wait_vmcnt<(C::NS - 2) * (C::L + 1)>(); else wait_vmcnt<(C::NS - 2) * C::L>();
+  } else {
+    wait_vmcnt<0>();
+  }
   __builtin_amdgcn_s_barrier();
   static_for<12>([&](auto uc) { read_unit(h0, 0u, IntC<0>{}, uc); });
-  WAIT_HALVES(h0);
-  mask_halves(h0, 0, 0);
+  he0[0] = he0[1] = he1[0] = he1[1] = bf16x4{};
+  if (has_edge) read_edge(he0, 0u, IntC<0>{});
+  WAIT_HALVES_E(h0, he0);
+  mask_halves(h0, he0, 0, 0);
 
   // One slab: sixteen MFMAs in two steps of eight, numbered i = 2a + b within a
   // step.  The twelve transpose reads of the next step follow MFMAs 0-2 (four
@@ -502,16 +584,21 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   // steady-state form (kt mod NS known at compile time, a later slab always
   // fetched, nothing ragged): no branch, no address arithmetic.  KM < 0 is the
   // general form used for the last slabs.
-  auto do_slab = [&](int kt, auto kmc) {
+  auto do_slab = [&](int kt, auto kmc, auto edgec) {
     constexpr int KM = decltype(kmc)::value;
-    constexpr bool FAST = KM >= 0;
+    constexpr bool FAST = KM >= 0, EDGE = decltype(edgec)::value;
     // slab kt+1 has landed once at most the NS-3 younger slabs are outstanding
-    if (FAST || kt + C::NS - 2 < nk) wait_vmcnt<(C::NS - 3) * C::L>(); else wait_vmcnt<0>();
+    if (FAST || kt + C::NS - 2 < nk) {
+      if (EDGE && wave == 0) wait_vmcnt<(C::NS - 3) * (C::L + 1)>(); else wait_vmcnt<(C::NS - 3) * C::L>();
+    } else {
+      wait_vmcnt<0>();
+    }
     __builtin_amdgcn_s_barrier();
     const bool fetch = FAST || kt + C::NS - 1 < nk;
     const bool more = FAST || kt + 1 < nk;
     const unsigned so = (unsigned)((kt % C::NS) * C::STAGE_BYTES);
     const unsigned so_next = (unsigned)(((kt + 1) % C::NS) * C::STAGE_BYTES);
+    constexpr int ST_FETCH = FAST ? (KM + C::NS - 1) % C::NS : -1;
     static_for<8>([&](auto ic) {
       constexpr int i = decltype(ic)::value, a = i / 2, b = i % 2;
       __builtin_amdgcn_sched_barrier(0);
@@ -524,14 +611,21 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
           else read_unit(h1, so, IntC<1>{}, IntC<u>{});
         });
       } else if constexpr (i < 7) {
-        if constexpr (FAST) issue_one(IntC<i - 3>{}, IntC<(KM >= 0 ? (KM + C::NS - 1) % C::NS : 0)>{});
+        if constexpr (EDGE && i == 3) {
+          if constexpr (FAST) read_edge_at(he1, IntC<(KM >= 0 ? KM : 0)>{}, IntC<1>{});
+          else read_edge(he1, so, IntC<1>{});
+        }
+        if constexpr (FAST) issue_one(IntC<i - 3>{}, IntC<ST_FETCH>{});
         else if (fetch) issue_one(IntC<i - 3>{}, IntC<-1>{});
+      } else if constexpr (EDGE) {
+        if (fetch && wave == 0) issue_edge(IntC<ST_FETCH>{});
       }
     });
+    if constexpr (EDGE) edge_mma(he0, h0);
     if (fetch) ++next_fetch;
     __builtin_amdgcn_sched_barrier(0);
-    WAIT_HALVES(h1);
-    if constexpr (!FAST) mask_halves(h1, kt, 1);
+    if constexpr (EDGE) WAIT_HALVES_E(h1, he1); else WAIT_HALVES(h1);
+    if constexpr (!FAST) mask_halves(h1, he1, kt, 1);
     static_for<8>([&](auto ic) {
       constexpr int i = decltype(ic)::value, a = i / 2, b = i % 2;
       __builtin_amdgcn_sched_barrier(0);
@@ -543,12 +637,16 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
           if constexpr (FAST) read_unit_at(h0, IntC<(KM >= 0 ? (KM + 1) % C::NS : 0)>{}, IntC<0>{}, IntC<u>{});
           else if (more) read_unit(h0, so_next, IntC<0>{}, IntC<u>{});
         });
+      } else if constexpr (EDGE && i == 3) {
+        if constexpr (FAST) read_edge_at(he0, IntC<(KM >= 0 ? (KM + 1) % C::NS : 0)>{}, IntC<0>{});
+        else if (more) read_edge(he0, so_next, IntC<0>{});
       }
     });
+    if constexpr (EDGE) edge_mma(he1, h1);
     __builtin_amdgcn_sched_barrier(0);
     if (more) {
-      WAIT_HALVES(h0);
-      if constexpr (!FAST) mask_halves(h0, kt + 1, 0);
+      if constexpr (EDGE) WAIT_HALVES_E(h0, he0); else WAIT_HALVES(h0);
+      if constexpr (!FAST) mask_halves(h0, he0, kt + 1, 0);
     }
   };
 
@@ -556,10 +654,13 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   // groups of NS so that the ring slot is a compile-time constant.
   const bool last_ragged = (klen % C::BK) != 0;
   const int n_fast = (nk - (C::NS - 1) - (last_ragged ? 1 : 0)) / C::NS * C::NS;
-  int kt = 0;
-  for (; kt < n_fast; kt += C::NS)
-    static_for<C::NS>([&](auto kmc) { do_slab(kt + decltype(kmc)::value, kmc); });
-  for (; kt < nk; ++kt) do_slab(kt, IntC<-1>{});
+  auto run_slabs = [&](auto edgec) {
+    int kt = 0;
+    for (; kt < n_fast; kt += C::NS)
+      static_for<C::NS>([&](auto kmc) { do_slab(kt + decltype(kmc)::value, kmc, edgec); });
+    for (; kt < nk; ++kt) do_slab(kt, IntC<-1>{}, edgec);
+  };
+  if (has_edge) run_slabs(IntC<1>{}); else run_slabs(IntC<0>{});
 
   // ---- epilogue.  Accumulator register v of a 32x32 block holds
   // row (v / 4) * 8 + (lane / 32) * 4 + v % 4, column lane % 32 -- a layout that
@@ -592,6 +693,21 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
                                : (void*)((float*)q.s.W + i + p.begin);
     return d;
   };
+  if (has_edge) {
+    // Edge block: MFMA rows 0-7 are the leading group, 8-15 the group of the trailing row
+    // (registers v = 0..7 of the block); one element at a time, masked by the chunk's range.
+    const int64_t col = col0 + wn0 + (wave >> 2) * 32 + (lane & 31);
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+      const int r8 = (lane >> 5) * 4 + (v & 3);
+      int64_t row;
+      if (v < 4) row = q.lead_base >= 0 ? q.lead_base + r8 : -1;
+      else row = (q.trail_row >= 0 && (q.trail_row & 7) == r8) ? q.trail_row : -1;
+      const int64_t flat = row * p.in + col;
+      if (row >= 0 && col < p.in && flat >= p.begin && flat < p.end)
+        emit<MODE>(q.s, E, slab, flat - p.begin, flat, acc_e[v]);
+    }
+  }
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     __syncthreads();                       // ring reads / previous half's row reads are done
@@ -902,7 +1018,8 @@ Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T
 template <class C>
 int launch_mfma_cfg(const WgradProblem& p, int mode, const Sinks& s, hipStream_t st) {
   const RowSplit rs = split_rows(p);
-  if (rs.lead_base >= 0 || rs.trail_row >= 0) {
+  const bool body = rs.rb1 > rs.rb0;
+  if (!body && (rs.lead_base >= 0 || rs.trail_row >= 0)) {
     EdgeParams e{};
     e.p = p;
     e.s = s;
@@ -924,6 +1041,8 @@ int launch_mfma_cfg(const WgradProblem& p, int mode, const Sinks& s, hipStream_t
   q.s = s;
   q.rb0 = rs.rb0;
   q.rb1 = rs.rb1;
+  q.lead_base = rs.lead_base;
+  q.trail_row = rs.trail_row;
   q.tiles_m = (int32_t)ceil_div(rs.rb1 - rs.rb0, C::BM);
   q.tiles_n = (int32_t)ceil_div(p.in, C::BN);
   const int64_t n_items = (int64_t)q.tiles_m * q.tiles_n * p.S;
