@@ -30,9 +30,10 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0        # HBM3E
 
-# HBM bytes per launch from rocprofv3 --pmc runs (FETCH_SIZE / WRITE_SIZE scaled by a
-# copy kernel of known size); None until such a run is summarised under profiles/.
-MEASURED_TRAFFIC = {"wgrad": None, "adamw": None, "fused": None}
+# HBM bytes per launch at this workload from rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE,
+# each scaled by what the counter reads for the plain copy of --copy-probe: x2.000 and x1.000);
+# the summary of those runs is profiles/bench_llama8b_upproj_hbm_traffic.txt.
+MEASURED_TRAFFIC = {"wgrad": 265.6e6, "adamw": 1011.9e6, "fused": 1101.3e6}
 
 
 def main():
@@ -41,6 +42,10 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="after the timed region, run a plain device copy of known size (256 MiB read, "
+                         "256 MiB written, three times): the calibration point for rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path has no collective); use --gpus 1",
@@ -151,7 +156,8 @@ def main():
                   "bound": "hbm", "bound_ms": round(fused_bound_ms, 4),
                   "frac_of_bound": round(fused_bound_ms / ms["fused"], 4),
                   "gbps": round(fused_bytes / (ms["fused"] * 1e-3) / 1e9, 1),
-                  "tflops": round(flops / (ms["fused"] * 1e-3) / 1e12, 2)},
+                  "tflops": round(flops / (ms["fused"] * 1e-3) / 1e12, 2),
+                  "traffic": MEASURED_TRAFFIC["fused"], "algorithmic_bytes": fused_bytes},
         "roofline": {"kernel": "wgrad_mfma_kernel (chunkft_chunk_wgrad)", "bound": "mfma",
                      "achieved": round(wgrad_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(wgrad_tflops / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC["wgrad"],
@@ -161,6 +167,15 @@ def main():
                            "frac": round(adamw_gbps / PEAK_HBM_GBPS, 4), "traffic": MEASURED_TRAFFIC["adamw"],
                            "algorithmic_bytes": adamw_bytes},
     }
+
+    if args.copy_probe:
+        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)          # one element-wise kernel: 4 B read + 4 B written per element
+        torch.cuda.synchronize()
+        out["copy_probe"] = {"kernel": "torch.mul(src, 1.0, out=dst)", "read_bytes": src.numel() * 4,
+                             "write_bytes": src.numel() * 4}
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(case, begin, end, hp)
