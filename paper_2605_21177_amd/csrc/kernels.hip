@@ -179,6 +179,7 @@ struct MfmaParams {
   int32_t tiles_m, tiles_n;
   int32_t n_tile_items;        // tiles_m * tiles_n * S
   int32_t group_m;
+  int32_t stagger;             // start delay of every second resident workgroup, in units of 8128 cycles
   int64_t lead_base;           // edge rows folded into the first tile row (-1: none), as in EdgeParams
   int64_t trail_row;
   Sinks s;
@@ -191,12 +192,16 @@ struct EdgeParams {
   Sinks s;
 };
 
-// Tile configuration of the MFMA kernel: a 256 x 256 output tile per workgroup
-// of 8 waves (2 x 4, each wave 128 x 64 = 4 x 2 blocks of 32 x 32), tokens in
+// Tile configuration of the MFMA kernel: a (128 WM) x 256 output tile per workgroup
+// of 4 WM waves (WM x 4, each wave 128 x 64 = 4 x 2 blocks of 32 x 32), tokens in
 // slabs of 32, and a ring of NS slabs in LDS filled by global->LDS loads.
-template <int NS_>
+//   WM = 1, NS = 3: 128 x 256 tiles, 4 waves, 75 KB of LDS -- two workgroups share a
+//   compute unit, so the store-bound epilogue of one runs under the MFMA loop of the other;
+//   WM = 2, NS = 4: 256 x 256 tiles, 8 waves, 132 KB -- one workgroup per compute unit,
+//   a third less operand traffic per flop.
+template <int WM_, int NS_>
 struct RingCfg {
-  static constexpr int BM = 256, BN = 256, BK = 32, WM = 2, WN = 4, NS = NS_;
+  static constexpr int WM = WM_, WN = 4, BM = 128 * WM, BN = 256, BK = 32, NS = NS_;
   static constexpr int NW = WM * WN, NT = 64 * NW;
   static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   static constexpr int A_BYTES = BK * BM * 2, B_BYTES = BK * BN * 2;
@@ -207,13 +212,15 @@ struct RingCfg {
   static constexpr int LA = A_BYTES / 1024 / NW;     // 1 KB wave-loads per wave per slab
   static constexpr int LB = B_BYTES / 1024 / NW;
   static constexpr int L = LA + LB;
-  // epilogue staging: half a tile (128 rows x 256 columns of fp32) at a time; a row
+  // epilogue staging: half a tile (BM / 2 rows x 256 columns of fp32) at a time; a row
   // pitch of 264 floats puts the two half-waves of a ds_write_b32 on disjoint banks
   static constexpr int EPI_PITCH = BN + 8;
   static constexpr size_t EPI_BYTES = (size_t)(BM / 2) * EPI_PITCH * 4;
   static constexpr size_t RING_BYTES = (size_t)NS * STAGE_BYTES;
   static constexpr size_t LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
-  static_assert(TM == 4 && TN == 2 && L == 4 && NS >= 3, "the main loop is written out for this shape");
+  static constexpr int RA = BM * 2, RB = BN * 2;     // bytes of one token in the A / B image of a slab
+  static_assert(TM == 4 && TN == 2 && (WM == 1 || WM == 2) && L >= 4 && L <= 6 && NS >= 3,
+                "the main loop is written out for this shape");
 };
 
 // Edge rows: the leading ones all lie in one 8-aligned group of rows (one 16-byte
@@ -325,12 +332,13 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 //
 // Schedule.  Per 32-token slab a wave issues 16 MFMAs in two 16-token steps.
 // The transpose reads of the NEXT step are issued behind the first three MFMAs
-// of a step and the global->LDS loads of a later slab behind the following four,
-// so their latency runs under the remaining MFMAs instead of in front of a wait.
-// One s_barrier per slab: it publishes slab kt+1 (every wave waited for its own
-// loads of it) and retires slab kt-1, whose buffer the new loads overwrite.
+// of a step and the global->LDS loads of a later slab behind the last five of the
+// second step, so their latency runs under MFMAs instead of in front of a wait.
+// One s_barrier per slab, between its two steps: it publishes slab kt+1 (every
+// wave waited for its own loads of it) and retires slab kt, whose ring slot the
+// loads of slab kt+NS then overwrite -- the whole ring is in flight.
 template <class C, int MODE>
-__global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
+__global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char ldsb[];
   const WgradProblem& p = q.p;
 
@@ -341,6 +349,17 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   const int per_xcd = (n_items + 7) >> 3;
   const int item = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
   if (item >= n_items) return;
+
+  // Two workgroups share a compute unit.  Started together they run their MFMA loops
+  // together and then their HBM-bound epilogues together; with q.stagger > 0 the second
+  // one of each pair (workgroups are dealt to the 32 compute units of an XCD in order:
+  // the first 32 fill one slot each, the next 32 the other) starts late instead, so that
+  // one tends to be in its loop while the other is in its epilogue.
+  if constexpr (C::WM == 1) {
+    const int j = (int)(blockIdx.x >> 3);
+    if (j >= 32 && j < 64)
+      for (int i = 0; i < q.stagger; ++i) __builtin_amdgcn_s_sleep(127);
+  }
 
   // ---- which tile, which token slab
   const int n_tiles = q.tiles_m * q.tiles_n;
@@ -377,10 +396,13 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   const unsigned short* pa[C::LA];
   const unsigned short* pb[C::LB];
   int ka[C::LA], kb[C::LB];
+  // A wave-load writes 1 KB: 1024 / RA tokens, RA / 16 lanes (16-byte slots) per token.
+  constexpr int LPT_A = C::RA / 16, TPL_A = 64 / LPT_A;
 #pragma unroll
   for (int i = 0; i < C::LA; ++i) {
-    const int k = 2 * (wave * C::LA + i) + (lane >> 5);
-    const int lc = (lane & 31) ^ (((k & 3) | (((k >> 3) & 1) << 2)) << 2);
+    const int k = TPL_A * (wave * C::LA + i) + lane / LPT_A;
+    const int swk = C::WM == 2 ? ((k & 3) | (((k >> 3) & 1) << 2)) : (k & 3);
+    const int lc = (lane % LPT_A) ^ (swk << 2);
     int64_t r = row0 + lc * 8;
     if (r >= p.out) r = row0;
     ka[i] = k;
@@ -404,12 +426,16 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   // wave 0: lane l fetches, for token l/2, the 8-row group of the leading edge rows
   // (l even) or the one holding the trailing row (l odd); a missing group is
   // replaced by the tile's first rows (valid memory, masked in the epilogue).
-  const bool has_edge = tile_m == 0 && (q.lead_base >= 0 || q.trail_row >= 0);
+  // With 8 waves, waves w and w + 4 share 64 columns and take one of the two 32-column
+  // blocks each (workgroups of tile row 0); with 4 waves the workgroups of tile rows 0 and
+  // 1 take one block each (the launcher folds the edge in only if there are two tile rows).
+  const bool has_edge = (C::WM == 2 ? tile_m == 0 : tile_m < 2) && (q.lead_base >= 0 || q.trail_row >= 0);
+  const int edge_blk = C::WM == 2 ? (wave >> 2) : tile_m;
   const int ke = lane >> 1;
   const unsigned short* ge;
   {
-    const int64_t lead = q.lead_base >= 0 ? q.lead_base : row0;
-    const int64_t trail = q.trail_row >= 0 ? (q.trail_row & ~(int64_t)7) : row0;
+    const int64_t lead = q.lead_base >= 0 ? q.lead_base : q.rb0;
+    const int64_t trail = q.trail_row >= 0 ? (q.trail_row & ~(int64_t)7) : q.rb0;
     ge = dY + ((lane & 1) ? trail : lead);
   }
   const unsigned short* pe = ge + (k_begin + ke) * p.lddy;
@@ -474,12 +500,12 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   unsigned addrA[C::TM], addrB[C::TN], addrA_hi[C::TM], addrB_hi[C::TN];
 #pragma unroll
   for (int a = 0; a < C::TM; ++a) {
-    addrA[a] = lds_base + tr_k * 512 + ((((wm0 >> 3) + a * 4) ^ (swl << 2)) + low) * 16 + sub;
+    addrA[a] = lds_base + tr_k * C::RA + ((((wm0 >> 3) + a * 4) ^ ((C::WM == 2 ? swl : (i16 >> 2)) << 2)) + low) * 16 + sub;
     addrA_hi[a] = addrA[a] + 65536;
   }
 #pragma unroll
   for (int b = 0; b < C::TN; ++b) {
-    addrB[b] = lds_base + C::A_BYTES + tr_k * 512 + ((((wn0 >> 3) + b * 4) ^ (swl << 2)) + low) * 16 + sub;
+    addrB[b] = lds_base + C::A_BYTES + tr_k * C::RB + ((((wn0 >> 3) + b * 4) ^ (swl << 2)) + low) * 16 + sub;
     addrB_hi[b] = addrB[b] + 65536;
   }
 
@@ -504,10 +530,10 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
     he[0] = lds_tr_read<off>(so < 65536 ? addrE : addrE_hi);
     he[1] = lds_tr_read<off + 4 * 32>(so < 65536 ? addrE : addrE_hi);
   };
-  // the edge MFMA of a wave uses its B block wave / 4: waves w and w + 4 share their 64 columns
+  // the edge MFMA of a wave uses one of its two B blocks
   auto edge_mma = [&](const bf16x4* he, const bf16x4* h) {
     const bf16x8 fe = __builtin_shufflevector(he[0], he[1], 0, 1, 2, 3, 4, 5, 6, 7);
-    if (wave < 4) acc_e = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fe, __builtin_shufflevector(h[8], h[9], 0, 1, 2, 3, 4, 5, 6, 7), acc_e, 0, 0, 0);
+    if (edge_blk == 0) acc_e = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fe, __builtin_shufflevector(h[8], h[9], 0, 1, 2, 3, 4, 5, 6, 7), acc_e, 0, 0, 0);
     else acc_e = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fe, __builtin_shufflevector(h[10], h[11], 0, 1, 2, 3, 4, 5, 6, 7), acc_e, 0, 0, 0);
   };
 
@@ -516,14 +542,14 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   bf16x4 h0[12], h1[12];
   auto read_unit = [&](bf16x4* h, unsigned so, auto ksc, auto uc) {
     constexpr int ks = decltype(ksc)::value, u = decltype(uc)::value;
-    constexpr int off = (ks * 16 + (u & 1) * 4) * 512;
+    constexpr int off = (ks * 16 + (u & 1) * 4) * (u < 8 ? C::RA : C::RB);
     if constexpr (u < 8) h[u] = lds_tr_read<off>(addrA[u / 2] + so);
     else h[u] = lds_tr_read<off>(addrB[(u - 8) / 2] + so);
   };
   auto read_unit_at = [&](bf16x4* h, auto stagec, auto ksc, auto uc) {      // ring slot at compile time
     constexpr int st = decltype(stagec)::value, ks = decltype(ksc)::value, u = decltype(uc)::value;
     constexpr int so = st * C::STAGE_BYTES;
-    constexpr int off = (so & 0xFFFF) + (ks * 16 + (u & 1) * 4) * 512;
+    constexpr int off = (so & 0xFFFF) + (ks * 16 + (u & 1) * 4) * (u < 8 ? C::RA : C::RB);
     static_assert(off < 65536, "LDS offset field");
     if constexpr (u < 8) h[u] = lds_tr_read<off>(so < 65536 ? addrA[u / 2] : addrA_hi[u / 2]);
     else h[u] = lds_tr_read<off>(so < 65536 ? addrB[(u - 8) / 2] : addrB_hi[(u - 8) / 2]);
@@ -555,9 +581,9 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-  // ---- prologue: NS-1 slabs in flight, first step of slab 0 in registers
+  // ---- prologue: the whole ring (NS slabs) in flight, first step of slab 0 in registers
 #pragma unroll
-  for (int s = 0; s < C::NS - 1; ++s)
+  for (int s = 0; s < C::NS; ++s)
     if (s < nk) {
       static_for<C::L>([&](auto ic) { issue_one(ic, IntC<-1>{}); });
       if (has_edge && wave == 0) issue_edge(IntC<-1>{});
@@ -565,8 +591,8 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
     }
   // wave 0 of an edge workgroup has one more load per slab in flight than the others
   const bool five = has_edge && wave == 0;
-  if (C::NS - 2 < nk) {
-    if (five) wait_vmcnt<(C::NS - 2) * (C::L + 1)>(); else wait_vmcnt<(C::NS - 2) * C::L>();
+  if (C::NS - 1 < nk) {
+    if (five) wait_vmcnt<(C::NS - 1) * (C::L + 1)>(); else wait_vmcnt<(C::NS - 1) * C::L>();
   } else {
     wait_vmcnt<0>();
   }
@@ -579,26 +605,23 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
 
   // One slab: sixteen MFMAs in two steps of eight, numbered i = 2a + b within a
   // step.  The twelve transpose reads of the next step follow MFMAs 0-2 (four
-  // each), so the last of them has five MFMAs of time to return; the four
-  // global->LDS loads follow MFMAs 3-6 of the first step.  KM >= 0 is the
-  // steady-state form (kt mod NS known at compile time, a later slab always
-  // fetched, nothing ragged): no branch, no address arithmetic.  KM < 0 is the
-  // general form used for the last slabs.
+  // each), so the last of them has five MFMAs of time to return.  Between the two
+  // steps sits the slab's one barrier: before it every wave has finished reading
+  // ring slot kt (the reads of the second step were waited for) and has seen its
+  // own loads of slab kt+1 land, so behind it slot kt is free -- the loads of
+  // slab kt+NS go there, behind MFMAs 3-7 of the second step -- and slab kt+1 is
+  // complete for the reads of that step.  A slab thus has NS-1 slab times to
+  // arrive.  KM >= 0 is the steady-state form (kt mod NS known at compile time,
+  // a later slab always fetched, nothing ragged): no branch, no address
+  // arithmetic.  KM < 0 is the general form used for the last slabs.
   auto do_slab = [&](int kt, auto kmc, auto edgec) {
     constexpr int KM = decltype(kmc)::value;
     constexpr bool FAST = KM >= 0, EDGE = decltype(edgec)::value;
-    // slab kt+1 has landed once at most the NS-3 younger slabs are outstanding
-    if (FAST || kt + C::NS - 2 < nk) {
-      if (EDGE && wave == 0) wait_vmcnt<(C::NS - 3) * (C::L + 1)>(); else wait_vmcnt<(C::NS - 3) * C::L>();
-    } else {
-      wait_vmcnt<0>();
-    }
-    __builtin_amdgcn_s_barrier();
-    const bool fetch = FAST || kt + C::NS - 1 < nk;
+    const bool fetch = FAST || kt + C::NS < nk;
     const bool more = FAST || kt + 1 < nk;
     const unsigned so = (unsigned)((kt % C::NS) * C::STAGE_BYTES);
     const unsigned so_next = (unsigned)(((kt + 1) % C::NS) * C::STAGE_BYTES);
-    constexpr int ST_FETCH = FAST ? (KM + C::NS - 1) % C::NS : -1;
+    constexpr int ST_FETCH = FAST ? KM : -1;
     static_for<8>([&](auto ic) {
       constexpr int i = decltype(ic)::value, a = i / 2, b = i % 2;
       __builtin_amdgcn_sched_barrier(0);
@@ -610,22 +633,22 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
           if constexpr (FAST) read_unit_at(h1, IntC<(KM >= 0 ? KM : 0)>{}, IntC<1>{}, IntC<u>{});
           else read_unit(h1, so, IntC<1>{}, IntC<u>{});
         });
-      } else if constexpr (i < 7) {
-        if constexpr (EDGE && i == 3) {
-          if constexpr (FAST) read_edge_at(he1, IntC<(KM >= 0 ? KM : 0)>{}, IntC<1>{});
-          else read_edge(he1, so, IntC<1>{});
-        }
-        if constexpr (FAST) issue_one(IntC<i - 3>{}, IntC<ST_FETCH>{});
-        else if (fetch) issue_one(IntC<i - 3>{}, IntC<-1>{});
-      } else if constexpr (EDGE) {
-        if (fetch && wave == 0) issue_edge(IntC<ST_FETCH>{});
+      } else if constexpr (EDGE && i == 3) {
+        if constexpr (FAST) read_edge_at(he1, IntC<(KM >= 0 ? KM : 0)>{}, IntC<1>{});
+        else read_edge(he1, so, IntC<1>{});
       }
     });
     if constexpr (EDGE) edge_mma(he0, h0);
-    if (fetch) ++next_fetch;
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (EDGE) WAIT_HALVES_E(h1, he1); else WAIT_HALVES(h1);
     if constexpr (!FAST) mask_halves(h1, he1, kt, 1);
+    // slab kt+1 has landed once at most the NS-2 younger slabs are outstanding
+    if (FAST || kt + C::NS - 1 < nk) {
+      if (EDGE && wave == 0) wait_vmcnt<(C::NS - 2) * (C::L + 1)>(); else wait_vmcnt<(C::NS - 2) * C::L>();
+    } else {
+      wait_vmcnt<0>();
+    }
+    __builtin_amdgcn_s_barrier();
     static_for<8>([&](auto ic) {
       constexpr int i = decltype(ic)::value, a = i / 2, b = i % 2;
       __builtin_amdgcn_sched_barrier(0);
@@ -637,11 +660,25 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
           if constexpr (FAST) read_unit_at(h0, IntC<(KM >= 0 ? (KM + 1) % C::NS : 0)>{}, IntC<0>{}, IntC<u>{});
           else if (more) read_unit(h0, so_next, IntC<0>{}, IntC<u>{});
         });
-      } else if constexpr (EDGE && i == 3) {
-        if constexpr (FAST) read_edge_at(he0, IntC<(KM >= 0 ? (KM + 1) % C::NS : 0)>{}, IntC<0>{});
-        else if (more) read_edge(he0, so_next, IntC<0>{});
+      } else {
+        if constexpr (EDGE && i == 3) {
+          if constexpr (FAST) read_edge_at(he0, IntC<(KM >= 0 ? (KM + 1) % C::NS : 0)>{}, IntC<0>{});
+          else if (more) read_edge(he0, so_next, IntC<0>{});
+        }
+        // loads of slab kt+NS: one behind each of MFMAs 3-6, the rest behind MFMA 7
+        static_for<C::L>([&](auto lc) {
+          constexpr int l = decltype(lc)::value;
+          if constexpr ((l < 4 ? l + 3 : 7) == i) {
+            if constexpr (FAST) issue_one(lc, IntC<ST_FETCH>{});
+            else if (fetch) issue_one(lc, IntC<-1>{});
+          }
+        });
+        if constexpr (EDGE && i == 7) {
+          if (fetch && wave == 0) issue_edge(IntC<ST_FETCH>{});
+        }
       }
     });
+    if (fetch) ++next_fetch;
     if constexpr (EDGE) edge_mma(he1, h1);
     __builtin_amdgcn_sched_barrier(0);
     if (more) {
@@ -650,10 +687,11 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
     }
   };
 
-  // Steady state: slabs whose fetch (of slab kt + NS - 1) exists and is complete, in
+  // Steady state: slabs whose fetch (of slab kt + NS) exists and is complete, in
   // groups of NS so that the ring slot is a compile-time constant.
   const bool last_ragged = (klen % C::BK) != 0;
-  const int n_fast = (nk - (C::NS - 1) - (last_ragged ? 1 : 0)) / C::NS * C::NS;
+  const int n_fast_raw = (nk - C::NS - (last_ragged ? 1 : 0)) / C::NS * C::NS;
+  const int n_fast = n_fast_raw > 0 ? n_fast_raw : 0;
   auto run_slabs = [&](auto edgec) {
     int kt = 0;
     for (; kt < n_fast; kt += C::NS)
@@ -674,6 +712,7 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   const int cols_valid = (int)((p.in - col0 < C::BN) ? p.in - col0 : C::BN);
   float* const stage = reinterpret_cast<float*>(ldsb);
   const int wmi = wave / C::WN;
+  constexpr int HALF_ROWS = C::BM / 2;   // rows staged per pass: 64 per wave row
   float* const g_dst = MODE == EMIT_PARTIAL ? q.s.ws + (int64_t)slab * E : q.s.g;
   // Groups of four columns start where the fp32 destination is 16-byte aligned:
   // at tile-local column delta (the same for every row, because in % 8 == 0).
@@ -696,7 +735,7 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
   if (has_edge) {
     // Edge block: MFMA rows 0-7 are the leading group, 8-15 the group of the trailing row
     // (registers v = 0..7 of the block); one element at a time, masked by the chunk's range.
-    const int64_t col = col0 + wn0 + (wave >> 2) * 32 + (lane & 31);
+    const int64_t col = col0 + wn0 + edge_blk * 32 + (lane & 31);
 #pragma unroll
     for (int v = 0; v < 8; ++v) {
       const int r8 = (lane >> 5) * 4 + (v & 3);
@@ -726,7 +765,7 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
         bool ok[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const int rr = (j0 + u) * 8 + wave;                            // staged row, 0..127
+          const int rr = (j0 + u) * C::NW + wave;                        // staged row, 0..HALF_ROWS-1
           const int tile_row = (rr >> 6) * 128 + h * 64 + (rr & 63);
           ok[u] = tile_row < rows_valid;
           d[u] = sink_at(origin + (int64_t)tile_row * p.in + c4);
@@ -735,7 +774,7 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           if (ok[u]) {
-            const float* src = stage + ((j0 + u) * 8 + wave) * C::EPI_PITCH + c4;
+            const float* src = stage + ((j0 + u) * C::NW + wave) * C::EPI_PITCH + c4;
             const f32x4_u val = {src[0], src[1], src[2], src[3]};
             finish4<MODE>(d[u], q.s.w_kind, q.s.c, val, st[u]);
           }
@@ -743,6 +782,7 @@ __global__ __launch_bounds__(C::NT) void wgrad_mfma_kernel(const MfmaParams q) {
       }
     }
     if (delta != 0) {
+      static_assert(C::NT / 4 == HALF_ROWS, "one thread per left-over element of a staged half tile");
       const int rr = tid >> 2, e = tid & 3;
       const int tile_row = (rr >> 6) * 128 + h * 64 + (rr & 63);
       const int lc = e < delta ? e : cols_valid - 4 + e;      // cols_valid is a multiple of 8
@@ -941,7 +981,11 @@ constexpr int kNumCU = 256;
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-using MainCfg = RingCfg<4>;   // four slabs of 32 KB in LDS
+// Start delay (units of 8128 cycles) of the second workgroup of each compute unit in the fused
+// call, whose epilogue is long and HBM-bound: measured best at 4; the plain gradient gains nothing.
+constexpr int kStaggerAdamW = 4;
+using MainCfg = RingCfg<2, 4>;    // 256 x 256 tiles, four slabs of 33 KB in LDS, one workgroup per compute unit
+using FusedCfg = RingCfg<1, 3>;   // 128 x 256 tiles, three slabs of 25 KB, two workgroups per compute unit
 
 struct RowSplit {
   int64_t rb0, rb1;     // MFMA body rows [rb0, rb1), empty if rb1 <= rb0
@@ -1002,8 +1046,9 @@ Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T
     const int64_t rows = (end - 1) / in - begin / in + 1;
     const int64_t tiles = ceil_div(rows, bm) * ceil_div(in, bn);
     S = 1;
-    if (mfma && tiles < kNumCU) {
-      S = (2 * kNumCU) / tiles;                       // about two work items per CU
+    const int64_t slots = kNumCU;                     // resident workgroups
+    if (mfma && tiles < slots) {
+      S = (2 * slots) / tiles;                        // about two work items per slot
       const int64_t max_by_len = T / 256 > 0 ? T / 256 : 1;   // keep slabs of >= 256 tokens
       if (S > max_by_len) S = max_by_len;
       if (S > 64) S = 64;
@@ -1018,8 +1063,11 @@ Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T
 template <class C>
 int launch_mfma_cfg(const WgradProblem& p, int mode, const Sinks& s, hipStream_t st) {
   const RowSplit rs = split_rows(p);
-  const bool body = rs.rb1 > rs.rb0;
-  if (!body && (rs.lead_base >= 0 || rs.trail_row >= 0)) {
+  // the edge rows ride in the MFMA kernel if it has the tile rows that carry them
+  // (more than 128 body rows = two tile rows of the small tile; the same rule for both tile
+  // sizes, so that the fused and the plain call sum every element in the same order)
+  const bool folded = rs.rb1 - rs.rb0 > 128;
+  if (!folded && (rs.lead_base >= 0 || rs.trail_row >= 0)) {
     EdgeParams e{};
     e.p = p;
     e.s = s;
@@ -1041,24 +1089,33 @@ int launch_mfma_cfg(const WgradProblem& p, int mode, const Sinks& s, hipStream_t
   q.s = s;
   q.rb0 = rs.rb0;
   q.rb1 = rs.rb1;
-  q.lead_base = rs.lead_base;
-  q.trail_row = rs.trail_row;
+  q.lead_base = folded ? rs.lead_base : -1;
+  q.trail_row = folded ? rs.trail_row : -1;
   q.tiles_m = (int32_t)ceil_div(rs.rb1 - rs.rb0, C::BM);
   q.tiles_n = (int32_t)ceil_div(p.in, C::BN);
   const int64_t n_items = (int64_t)q.tiles_m * q.tiles_n * p.S;
   if (n_items > 0x3fffffff) return (int)hipErrorInvalidValue;
   q.n_tile_items = (int32_t)n_items;
   q.group_m = 8;
+  q.stagger = mode == EMIT_ADAMW ? kStaggerAdamW : 0;
   const int grid = (q.n_tile_items + 7) / 8 * 8;
-  switch (mode) {
-    case EMIT_STORE: return launch_mfma_mode<C, EMIT_STORE>(q, grid, st);
-    case EMIT_ACCUM: return launch_mfma_mode<C, EMIT_ACCUM>(q, grid, st);
-    case EMIT_PARTIAL: return launch_mfma_mode<C, EMIT_PARTIAL>(q, grid, st);
-    default: return launch_mfma_mode<C, EMIT_ADAMW>(q, grid, st);
+  if constexpr (C::WM == 1) {           // the small tile is built for the fused call only
+    if (mode != EMIT_ADAMW) return (int)hipErrorInvalidValue;
+    return launch_mfma_mode<C, EMIT_ADAMW>(q, grid, st);
+  } else {
+    switch (mode) {
+      case EMIT_STORE: return launch_mfma_mode<C, EMIT_STORE>(q, grid, st);
+      case EMIT_ACCUM: return launch_mfma_mode<C, EMIT_ACCUM>(q, grid, st);
+      case EMIT_PARTIAL: return launch_mfma_mode<C, EMIT_PARTIAL>(q, grid, st);
+      default: return (int)hipErrorInvalidValue;
+    }
   }
 }
 
 int launch_wgrad_bf16_mfma(const WgradProblem& p, int mode, const Sinks& s, void* stream) {
+  // The plain gradient (short epilogue) is a little faster on the large tile; the fused call,
+  // whose epilogue moves 26 bytes per element, gains from two workgroups per compute unit.
+  if (mode == EMIT_ADAMW) return launch_mfma_cfg<FusedCfg>(p, mode, s, (hipStream_t)stream);
   return launch_mfma_cfg<MainCfg>(p, mode, s, (hipStream_t)stream);
 }
 
