@@ -42,6 +42,10 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time the plain and the fused call at longer token counts (the same layer shape, "
+                         "T = 4096 and 8192) and on the lm_head shape of configs[4] per chunk size; "
+                         "reported under \"sweep\"")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region, run a plain device copy of known size (256 MiB read, "
                          "256 MiB written, three times): the calibration point for rocprofv3 --pmc "
@@ -120,6 +124,10 @@ def main():
     ms = {n: float(np.mean([a.elapsed_time(b) for a, b in ev[n]])) for n in names}
     ms_med = {n: float(np.median([a.elapsed_time(b) for a, b in ev[n]])) for n in names}
 
+    # what the matrix cores sustain on this device when fed from registers alone
+    ceil_const = B.chunkft_calib_mfma_bf16(False)
+    ceil_rand = B.chunkft_calib_mfma_bf16(True)
+
     flops = 2.0 * T * E
     R = (end - 1) // case.n_in - begin // case.n_in + 1
     wgrad_bytes = 2.0 * T * case.n_in + 2.0 * T * R + 4.0 * E        # X once, dY columns once, g once
@@ -161,12 +169,22 @@ def main():
         "roofline": {"kernel": "wgrad_mfma_kernel (chunkft_chunk_wgrad)", "bound": "mfma",
                      "achieved": round(wgrad_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(wgrad_tflops / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC["wgrad"],
-                     "algorithmic_bytes": wgrad_bytes},
+                     "algorithmic_bytes": wgrad_bytes,
+                     "mfma_only_measured": {
+                         "what": "32x32x16 bf16 MFMAs issued from registers, nothing else, two waves per SIMD "
+                                 "(chunkft_calib_mfma_bf16): the sustained clock, hence the reachable rate, "
+                                 "drops when the operands are random bit patterns as in a real contraction",
+                         "constant_operands": {"tflops": round(ceil_const[0], 1), "shader_mhz": round(ceil_const[1])},
+                         "random_operands": {"tflops": round(ceil_rand[0], 1), "shader_mhz": round(ceil_rand[1])},
+                         "frac_of_random_operand_rate": round(wgrad_tflops / ceil_rand[0], 4)}},
         "roofline_adamw": {"kernel": "elementwise_kernel (chunkft_adamw_chunk)", "bound": "hbm",
                            "achieved": round(adamw_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                            "frac": round(adamw_gbps / PEAK_HBM_GBPS, 4), "traffic": MEASURED_TRAFFIC["adamw"],
                            "algorithmic_bytes": adamw_bytes},
     }
+
+    if args.sweep:
+        out["sweep"] = sweep(torch, B, dev, dict(WL.HPARAMS))
 
     if args.copy_probe:
         src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
@@ -180,6 +198,56 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(case, begin, end, hp)
     print(json.dumps(out), flush=True)
+
+
+def sweep(torch, B, dev, hp):
+    """Plain and fused call on device-generated Gaussian operands of other shapes (same recipe:
+    X ~ N(0,1), dY ~ N(0,1e-3), two-scale token rows for the lm_head shape), median of 10."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(211770)
+    rows = []
+
+    def timed(fn, reps=10):
+        for _ in range(2):
+            fn()
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record(); b.synchronize()
+            ts.append(a.elapsed_time(b))
+        return sorted(ts)[len(ts) // 2]
+
+    def one(name, out_f, in_f, T, E, dy_scale):
+        X = torch.randn(T, in_f, device=dev, generator=gen).to(torch.bfloat16)
+        dY = (torch.randn(T, out_f, device=dev, generator=gen) * dy_scale).to(torch.bfloat16)
+        W = (torch.randn(out_f * in_f, device=dev, generator=gen) * 0.02).to(torch.bfloat16)
+        begin = (out_f * in_f - E) // 2 + 37
+        begin -= 1 if begin % in_f == 0 else 0
+        end = begin + E
+        layer = B.make_layer(B.LINEAR, X, dY, out_f, in_f)
+        nws = B.chunkft_workspace_bytes(layer, begin, end)
+        ws = torch.empty(max(nws // 4, 1), dtype=torch.float32, device=dev) if nws else None
+        g = torch.empty(E, dtype=torch.float32, device=dev)
+        master = W[begin:end].float()
+        m, v = torch.zeros_like(master), torch.zeros_like(master)
+        h = B.hparams(step=1, **hp)
+        t_w = timed(lambda: B.chunkft_chunk_wgrad(layer, begin, end, g, ws=ws))
+        t_f = timed(lambda: B.chunkft_wgrad_adamw_fused(layer, begin, end, W, master, m, v, h, ws=ws))
+        fl = 2.0 * T * E
+        R = (end - 1) // in_f - begin // in_f + 1
+        bound = max(fl / (PEAK_BF16_TFLOPS * 1e12), (26.0 * E + 2.0 * T * (in_f + R)) / (PEAK_HBM_GBPS * 1e9)) * 1e3
+        rows.append({"shape": name, "T": T, "chunk_MiB": E * 2 // (1 << 20),
+                     "split_k": B.chunkft_split_k(layer, begin, end),
+                     "wgrad_ms": round(t_w, 4), "wgrad_tflops": round(fl / t_w / 1e9, 1),
+                     "fused_ms": round(t_f, 4), "fused_tflops": round(fl / t_f / 1e9, 1),
+                     "fused_frac_of_bound": round(bound / t_f, 4)})
+
+    for T in (1024, 4096, 8192):
+        one("up_proj 14336x4096", 14336, 4096, T, 32 << 20, 1e-3)
+    scale = torch.where(torch.rand(4096, 1, device=dev, generator=gen) < 0.1, 1e-2, 1e-4)
+    for mib in (4, 16, 64, 256, 512):
+        one("lm_head 128256x4096", 128256, 4096, 4096, mib << 19, scale)
+    return rows
 
 
 def cpu_baseline(case, begin, end, hp):

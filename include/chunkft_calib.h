@@ -1,0 +1,39 @@
+/* Measurement aid of libchunkft: what the matrix cores of the device in use sustain.
+ *
+ * Not a step of the ChunkFT path.  The published dense bf16 rate of the part
+ * assumes its top clock; under a power cap the sustained clock, and with it the
+ * rate a contraction can reach, depends on how many operand bits change from one
+ * MFMA to the next.  The benchmark reports this measured ceiling beside the
+ * fraction of the published peak, so that a reader can tell kernel inefficiency
+ * from clock throttling.
+ */
+#ifndef CHUNKFT_CALIB_H
+#define CHUNKFT_CALIB_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Runs, on the current device, a kernel that issues nothing but 32x32x16 bf16
+ * MFMAs from registers (two waves per SIMD on every compute unit, eight
+ * independent accumulator blocks per wave as in the weight-gradient kernel) and
+ * times it with HIP events on `stream`.
+ *   random_operands  0: all operands are the constant 1.0 (few bits toggle);
+ *                    1: operands are random bf16 patterns with exponents around
+ *                       one, and every MFMA gets other registers than the one
+ *                       before it (the situation of a real contraction).
+ *   steps            MFMA steps of 8 instructions per wave; a multiple of 4, >= 4.
+ *   tflops           out (host): sustained rate, 2*32*32*16 flop per MFMA.
+ *   shader_mhz       out (host): clock during the kernel (shader cycle counter
+ *                    against the constant 100 MHz counter).
+ * Blocks until the measurement is done.  Uses one small device allocation that
+ * is freed before return.  Returns CHUNKFT_OK or a negative chunkft_status. */
+int chunkft_calib_mfma_bf16(int32_t random_operands, int32_t steps, double* tflops, double* shader_mhz,
+                            void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -100,13 +100,16 @@ def lib() -> C.CDLL:
         L.chunkft_status_string.argtypes = [C.c_int]
         L.chunkft_version.restype = C.c_int
         L.chunkft_version.argtypes = []
+        L.chunkft_calib_mfma_bf16.restype = C.c_int
+        L.chunkft_calib_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                              C.c_void_p]
         _lib = L
     return _lib
 
 
 EXPORTS = ("chunkft_plan_cycle", "chunkft_split_k", "chunkft_workspace_bytes", "chunkft_chunk_wgrad",
            "chunkft_adamw_chunk", "chunkft_wgrad_adamw_fused", "chunkft_status_string",
-           "chunkft_version")
+           "chunkft_version", "chunkft_calib_mfma_bf16")
 
 
 def status_string(status: int) -> str:
@@ -219,3 +222,13 @@ def chunkft_wgrad_adamw_fused(layer: Layer, begin: int, end: int, W, master, m, 
     if check and st != OK:
         raise ChunkFTError(st, "chunkft_wgrad_adamw_fused")
     return st
+
+
+def chunkft_calib_mfma_bf16(random_operands: bool, steps: int = 4000, stream=None) -> Tuple[float, float]:
+    """(TFLOP/s, shader MHz) that MFMAs issued from registers sustain on the current device."""
+    tf, mhz = C.c_double(0.0), C.c_double(0.0)
+    st = lib().chunkft_calib_mfma_bf16(1 if random_operands else 0, steps, C.byref(tf), C.byref(mhz),
+                                       _stream_ptr(stream))
+    if st != OK:
+        raise ChunkFTError(st, "chunkft_calib_mfma_bf16")
+    return tf.value, mhz.value

@@ -982,8 +982,9 @@ constexpr int kNumCU = 256;
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Start delay (units of 8128 cycles) of the second workgroup of each compute unit in the fused
-// call, whose epilogue is long and HBM-bound: measured best at 4; the plain gradient gains nothing.
-constexpr int kStaggerAdamW = 4;
+// call, whose epilogue is long and HBM-bound: measured best at 7-10 for 1024 to 8192 tokens; the
+// plain gradient gains nothing.
+constexpr int kStaggerAdamW = 8;
 using MainCfg = RingCfg<2, 4>;    // 256 x 256 tiles, four slabs of 33 KB in LDS, one workgroup per compute unit
 using FusedCfg = RingCfg<1, 3>;   // 128 x 256 tiles, three slabs of 25 KB, two workgroups per compute unit
 
