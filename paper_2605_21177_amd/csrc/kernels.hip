@@ -722,6 +722,10 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
   const int delta = (int)((4 - ((reinterpret_cast<uintptr_t>(align_ref) >> 2) + (uint64_t)origin) % 4) % 4);
   const int c4 = delta + lane * 4;
   const bool vec_lane = delta == 0 || lane < 63;
+  // The staged copy of a row is shifted right by sft columns, so that the groups of four
+  // that start at column delta sit on 16-byte boundaries in LDS too: one conflict-free
+  // 16-byte read per lane (the row pitch leaves room for the shift).
+  const int sft = (4 - delta) & 3;
   auto sink_at = [&](int64_t i) {
     Vec4Sink d;
     d.g = g_dst + i;
@@ -752,7 +756,7 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
     __syncthreads();                       // ring reads / previous half's row reads are done
     static_for<2 * C::TN>([&](auto blk_c) {
       constexpr int a2 = decltype(blk_c)::value / C::TN, b = decltype(blk_c)::value % C::TN;
-      float* base = stage + (wmi * 64 + a2 * 32 + (lane >> 5) * 4) * C::EPI_PITCH + wn0 + b * 32 + (lane & 31);
+      float* base = stage + (wmi * 64 + a2 * 32 + (lane >> 5) * 4) * C::EPI_PITCH + sft + wn0 + b * 32 + (lane & 31);
 #pragma unroll
       for (int v = 0; v < 16; ++v) base[((v >> 2) * 8 + (v & 3)) * C::EPI_PITCH] = acc[2 * h + a2][b][v];
     });
@@ -774,8 +778,8 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           if (ok[u]) {
-            const float* src = stage + ((j0 + u) * C::NW + wave) * C::EPI_PITCH + c4;
-            const f32x4_u val = {src[0], src[1], src[2], src[3]};
+            const float4 q4 = *reinterpret_cast<const float4*>(stage + ((j0 + u) * C::NW + wave) * C::EPI_PITCH + sft + c4);
+            const f32x4_u val = {q4.x, q4.y, q4.z, q4.w};
             finish4<MODE>(d[u], q.s.w_kind, q.s.c, val, st[u]);
           }
         }
@@ -788,7 +792,7 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
       const int lc = e < delta ? e : cols_valid - 4 + e;      // cols_valid is a multiple of 8
       if (tile_row < rows_valid) {
         const int64_t i = origin + (int64_t)tile_row * p.in + lc;
-        emit<MODE>(q.s, E, slab, i, i + p.begin, stage[rr * C::EPI_PITCH + lc]);
+        emit<MODE>(q.s, E, slab, i, i + p.begin, stage[rr * C::EPI_PITCH + sft + lc]);
       }
     }
   }
