@@ -317,6 +317,113 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
                : "+v"(h[0]), "+v"(h[1]), "+v"(h[2]), "+v"(h[3]), "+v"(h[4]), "+v"(h[5]), "+v"(h[6]),     \
                  "+v"(h[7]), "+v"(h[8]), "+v"(h[9]), "+v"(h[10]), "+v"(h[11]), "+v"(he[0]), "+v"(he[1])::"memory")
 
+// Epilogue of one tile of the MFMA kernels.  Accumulator register v of a 32x32 block holds
+// row (v / 4) * 8 + (lane / 32) * 4 + v % 4, column lane % 32 -- a layout that
+// could only be stored 4 bytes per lane.  The tile is therefore staged through
+// LDS (the ring is free by now), half of it at a time, and leaves as whole rows:
+// a wave handles one row of 256 columns per trip, 16 bytes per lane, 1 KB per
+// instruction, for the gradient as well as for the AdamW state.
+template <class C, int MODE>
+__device__ __forceinline__ void tile_epilogue(const MfmaParams& q, unsigned char* ldsb, int64_t row0, int64_t col0,
+                                              int slab, int wave, int lane, int tid,
+                                              f32x16 (&acc)[C::TM][C::TN], bool has_edge, int edge_blk,
+                                              const f32x16& acc_e) {
+  const WgradProblem& p = q.p;
+  const int wn0 = (wave % C::WN) * (C::BN / C::WN);
+  const int64_t E = p.end - p.begin;
+  const int64_t origin = row0 * p.in + col0 - p.begin;             // chunk-local index of the tile corner
+  const int rows_valid = (int)((q.rb1 - row0 < C::BM) ? q.rb1 - row0 : C::BM);
+  const int cols_valid = (int)((p.in - col0 < C::BN) ? p.in - col0 : C::BN);
+  float* const stage = reinterpret_cast<float*>(ldsb);
+  const int wmi = wave / C::WN;
+  constexpr int APH = C::TM / 2;          // 32-row accumulator blocks of a wave per half
+  constexpr int WR = 32 * APH;            // rows of one wave row in a staged half
+  constexpr int HALF_ROWS = C::WM * WR;   // rows staged per pass
+  float* const g_dst = MODE == EMIT_PARTIAL ? q.s.ws + (int64_t)slab * E : q.s.g;
+  // Groups of four columns start where the fp32 destination is 16-byte aligned:
+  // at tile-local column delta (the same for every row, because in % 8 == 0).
+  // The delta leading and 4 - delta trailing columns of a row that are left over
+  // are taken one element per thread (128 rows x 4 = 512 of them per half tile).
+  const float* const align_ref = MODE == EMIT_ADAMW ? q.s.master : g_dst;
+  const int delta = (int)((4 - ((reinterpret_cast<uintptr_t>(align_ref) >> 2) + (uint64_t)origin) % 4) % 4);
+  const int c4 = delta + lane * 4;
+  const bool vec_lane = delta == 0 || lane < 63;
+  // The staged copy of a row is shifted right by sft columns, so that the groups of four
+  // that start at column delta sit on 16-byte boundaries in LDS too: one conflict-free
+  // 16-byte read per lane (the row pitch leaves room for the shift).
+  const int sft = (4 - delta) & 3;
+  auto sink_at = [&](int64_t i) {
+    Vec4Sink d;
+    d.g = g_dst + i;
+    d.master = q.s.master + i;
+    d.m = q.s.m + i;
+    d.v = q.s.v + i;
+    d.W = q.s.w_kind == W_BF16 ? (void*)((unsigned short*)q.s.W + i + p.begin)
+                               : (void*)((float*)q.s.W + i + p.begin);
+    return d;
+  };
+  if (has_edge) {
+    // Edge block: MFMA rows 0-7 are the leading group, 8-15 the group of the trailing row
+    // (registers v = 0..7 of the block); one element at a time, masked by the chunk's range.
+    const int64_t col = col0 + wn0 + edge_blk * 32 + (lane & 31);
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+      const int r8 = (lane >> 5) * 4 + (v & 3);
+      int64_t row;
+      if (v < 4) row = q.lead_base >= 0 ? q.lead_base + r8 : -1;
+      else row = (q.trail_row >= 0 && (q.trail_row & 7) == r8) ? q.trail_row : -1;
+      const int64_t flat = row * p.in + col;
+      if (row >= 0 && col < p.in && flat >= p.begin && flat < p.end)
+        emit<MODE>(q.s, E, slab, flat - p.begin, flat, acc_e[v]);
+    }
+  }
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    __syncthreads();                       // ring reads / previous half's row reads are done
+    static_for<APH * C::TN>([&](auto blk_c) {
+      constexpr int a2 = decltype(blk_c)::value / C::TN, b = decltype(blk_c)::value % C::TN;
+      float* base = stage + (wmi * WR + a2 * 32 + (lane >> 5) * 4) * C::EPI_PITCH + sft + wn0 + b * 32 + (lane & 31);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) base[((v >> 2) * 8 + (v & 3)) * C::EPI_PITCH] = acc[h * APH + a2][b][v];
+    });
+    __syncthreads();
+    if (vec_lane && c4 + 4 <= cols_valid) {
+      // four rows per trip: their state loads are issued together, then the updates
+      for (int j0 = 0; j0 < HALF_ROWS / C::NW; j0 += 4) {
+        Vec4Sink d[4];
+        State4 st[4];
+        bool ok[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int rr = (j0 + u) * C::NW + wave;                        // staged row, 0..HALF_ROWS-1
+          const int tile_row = (rr / WR) * (2 * WR) + h * WR + rr % WR;
+          ok[u] = tile_row < rows_valid;
+          d[u] = sink_at(origin + (int64_t)tile_row * p.in + c4);
+          if (ok[u]) st[u] = load_state4<MODE>(d[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (ok[u]) {
+            const float4 q4 = *reinterpret_cast<const float4*>(stage + ((j0 + u) * C::NW + wave) * C::EPI_PITCH + sft + c4);
+            const f32x4_u val = {q4.x, q4.y, q4.z, q4.w};
+            finish4<MODE>(d[u], q.s.w_kind, q.s.c, val, st[u]);
+          }
+        }
+      }
+    }
+    if (delta != 0) {
+      static_assert(C::NT / 4 >= HALF_ROWS, "one thread per left-over element of a staged half tile");
+      const int rr = tid >> 2, e = tid & 3;
+      const int tile_row = (rr / WR) * (2 * WR) + h * WR + rr % WR;
+      const int lc = e < delta ? e : cols_valid - 4 + e;      // cols_valid is a multiple of 8
+      if (rr < HALF_ROWS && tile_row < rows_valid) {
+        const int64_t i = origin + (int64_t)tile_row * p.in + lc;
+        emit<MODE>(q.s, E, slab, i, i + p.begin, stage[rr * C::EPI_PITCH + sft + lc]);
+      }
+    }
+  }
+}
+
 // One 256 x 256 tile of body rows over one slab of tokens.
 //
 // Data movement.  dY and X are [token][row] / [token][column]: both operands have
@@ -700,102 +807,7 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
   };
   if (has_edge) run_slabs(IntC<1>{}); else run_slabs(IntC<0>{});
 
-  // ---- epilogue.  Accumulator register v of a 32x32 block holds
-  // row (v / 4) * 8 + (lane / 32) * 4 + v % 4, column lane % 32 -- a layout that
-  // could only be stored 4 bytes per lane.  The tile is therefore staged through
-  // LDS (the ring is free now), half of it at a time, and leaves as whole rows:
-  // a wave handles one row of 256 columns per trip, 16 bytes per lane, 1 KB per
-  // instruction, for the gradient as well as for the AdamW state.
-  const int64_t E = p.end - p.begin;
-  const int64_t origin = row0 * p.in + col0 - p.begin;             // chunk-local index of the tile corner
-  const int rows_valid = (int)((q.rb1 - row0 < C::BM) ? q.rb1 - row0 : C::BM);
-  const int cols_valid = (int)((p.in - col0 < C::BN) ? p.in - col0 : C::BN);
-  float* const stage = reinterpret_cast<float*>(ldsb);
-  const int wmi = wave / C::WN;
-  constexpr int HALF_ROWS = C::BM / 2;   // rows staged per pass: 64 per wave row
-  float* const g_dst = MODE == EMIT_PARTIAL ? q.s.ws + (int64_t)slab * E : q.s.g;
-  // Groups of four columns start where the fp32 destination is 16-byte aligned:
-  // at tile-local column delta (the same for every row, because in % 8 == 0).
-  // The delta leading and 4 - delta trailing columns of a row that are left over
-  // are taken one element per thread (128 rows x 4 = 512 of them per half tile).
-  const float* const align_ref = MODE == EMIT_ADAMW ? q.s.master : g_dst;
-  const int delta = (int)((4 - ((reinterpret_cast<uintptr_t>(align_ref) >> 2) + (uint64_t)origin) % 4) % 4);
-  const int c4 = delta + lane * 4;
-  const bool vec_lane = delta == 0 || lane < 63;
-  // The staged copy of a row is shifted right by sft columns, so that the groups of four
-  // that start at column delta sit on 16-byte boundaries in LDS too: one conflict-free
-  // 16-byte read per lane (the row pitch leaves room for the shift).
-  const int sft = (4 - delta) & 3;
-  auto sink_at = [&](int64_t i) {
-    Vec4Sink d;
-    d.g = g_dst + i;
-    d.master = q.s.master + i;
-    d.m = q.s.m + i;
-    d.v = q.s.v + i;
-    d.W = q.s.w_kind == W_BF16 ? (void*)((unsigned short*)q.s.W + i + p.begin)
-                               : (void*)((float*)q.s.W + i + p.begin);
-    return d;
-  };
-  if (has_edge) {
-    // Edge block: MFMA rows 0-7 are the leading group, 8-15 the group of the trailing row
-    // (registers v = 0..7 of the block); one element at a time, masked by the chunk's range.
-    const int64_t col = col0 + wn0 + edge_blk * 32 + (lane & 31);
-#pragma unroll
-    for (int v = 0; v < 8; ++v) {
-      const int r8 = (lane >> 5) * 4 + (v & 3);
-      int64_t row;
-      if (v < 4) row = q.lead_base >= 0 ? q.lead_base + r8 : -1;
-      else row = (q.trail_row >= 0 && (q.trail_row & 7) == r8) ? q.trail_row : -1;
-      const int64_t flat = row * p.in + col;
-      if (row >= 0 && col < p.in && flat >= p.begin && flat < p.end)
-        emit<MODE>(q.s, E, slab, flat - p.begin, flat, acc_e[v]);
-    }
-  }
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    __syncthreads();                       // ring reads / previous half's row reads are done
-    static_for<2 * C::TN>([&](auto blk_c) {
-      constexpr int a2 = decltype(blk_c)::value / C::TN, b = decltype(blk_c)::value % C::TN;
-      float* base = stage + (wmi * 64 + a2 * 32 + (lane >> 5) * 4) * C::EPI_PITCH + sft + wn0 + b * 32 + (lane & 31);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) base[((v >> 2) * 8 + (v & 3)) * C::EPI_PITCH] = acc[2 * h + a2][b][v];
-    });
-    __syncthreads();
-    if (vec_lane && c4 + 4 <= cols_valid) {
-      // four rows per trip: their state loads are issued together, then the updates
-      for (int j0 = 0; j0 < 16; j0 += 4) {
-        Vec4Sink d[4];
-        State4 st[4];
-        bool ok[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int rr = (j0 + u) * C::NW + wave;                        // staged row, 0..HALF_ROWS-1
-          const int tile_row = (rr >> 6) * 128 + h * 64 + (rr & 63);
-          ok[u] = tile_row < rows_valid;
-          d[u] = sink_at(origin + (int64_t)tile_row * p.in + c4);
-          if (ok[u]) st[u] = load_state4<MODE>(d[u]);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          if (ok[u]) {
-            const float4 q4 = *reinterpret_cast<const float4*>(stage + ((j0 + u) * C::NW + wave) * C::EPI_PITCH + sft + c4);
-            const f32x4_u val = {q4.x, q4.y, q4.z, q4.w};
-            finish4<MODE>(d[u], q.s.w_kind, q.s.c, val, st[u]);
-          }
-        }
-      }
-    }
-    if (delta != 0) {
-      static_assert(C::NT / 4 == HALF_ROWS, "one thread per left-over element of a staged half tile");
-      const int rr = tid >> 2, e = tid & 3;
-      const int tile_row = (rr >> 6) * 128 + h * 64 + (rr & 63);
-      const int lc = e < delta ? e : cols_valid - 4 + e;      // cols_valid is a multiple of 8
-      if (tile_row < rows_valid) {
-        const int64_t i = origin + (int64_t)tile_row * p.in + lc;
-        emit<MODE>(q.s, E, slab, i, i + p.begin, stage[rr * C::EPI_PITCH + sft + lc]);
-      }
-    }
-  }
+  tile_epilogue<C, MODE>(q, ldsb, row0, col0, slab, wave, lane, tid, acc, has_edge, edge_blk, acc_e);
 }
 
 // ---------------------------------------------------------------------------
@@ -1020,13 +1032,14 @@ RowSplit split_rows(const WgradProblem& p) {
 template <class C, int MODE>
 int launch_mfma_mode(const MfmaParams& q, int grid, hipStream_t st) {
   static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; a race only repeats it
+  const auto kern = &wgrad_mfma_kernel<C, MODE>;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)wgrad_mfma_kernel<C, MODE>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)C::LDS_BYTES);
     if (e != hipSuccess) return (int)e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((wgrad_mfma_kernel<C, MODE>), dim3(grid), dim3(C::NT), C::LDS_BYTES, st, q);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS_BYTES, st, q);
   return (int)hipGetLastError();
 }
 
@@ -1104,7 +1117,7 @@ int launch_mfma_cfg(const WgradProblem& p, int mode, const Sinks& s, hipStream_t
   q.group_m = 8;
   q.stagger = mode == EMIT_ADAMW ? kStaggerAdamW : 0;
   const int grid = (q.n_tile_items + 7) / 8 * 8;
-  if constexpr (C::WM == 1) {           // the small tile is built for the fused call only
+  if constexpr (C::WM == 1) {           // this tile is built for the fused call only
     if (mode != EMIT_ADAMW) return (int)hipErrorInvalidValue;
     return launch_mfma_mode<C, EMIT_ADAMW>(q, grid, st);
   } else {
