@@ -199,3 +199,13 @@ def test_product_path_does_not_import_the_oracle():
             if f.endswith((".py", ".cpp", ".hip", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.replace("no fallback", ""), f
+
+
+def test_calibration_call_validates_before_touching_the_device():
+    import ctypes as C
+    lib = B.lib()
+    tf, mhz = C.c_double(0.0), C.c_double(0.0)
+    bad = [(1, 0), (1, 6), (1, -4), (0, (1 << 20) + 4)]
+    for rnd, steps in bad:
+        assert lib.chunkft_calib_mfma_bf16(rnd, steps, C.byref(tf), C.byref(mhz), None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_calib_mfma_bf16(1, 8, None, C.byref(mhz), None) == B.ERR_INVALID_ARG
