@@ -22,8 +22,8 @@
  *   - Pointers marked (device) must be device memory reachable from the
  *     current HIP device; pointers marked (host) are ordinary host memory.
  *   - The library allocates no device memory and keeps no data between
- *     calls (its only process state is a flag per kernel that the kernel's
- *     LDS size attribute has been set).  Every buffer is owned by the caller.
+ *     calls (its only process state is a flag per kernel and device that the
+ *     kernel's LDS size attribute has been set).  Every buffer is owned by the caller.
  *   - Device entry points validate their arguments synchronously, then
  *     enqueue kernels on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) and return without waiting.  They return CHUNKFT_OK or
