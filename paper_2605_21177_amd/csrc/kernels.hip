@@ -1120,7 +1120,11 @@ int launch_mfma_cfg(const WgradProblem& p, int mode, const Sinks& s, hipStream_t
   const int64_t n_items = (int64_t)q.tiles_m * q.tiles_n * p.S;
   if (n_items > 0x3fffffff) return (int)hipErrorInvalidValue;
   q.n_tile_items = (int32_t)n_items;
-  q.group_m = 8;
+  // Order of the tiles inside an XCD's run of work items.  Plain gradient: groups of 8 tile rows,
+  // column tile by column tile (X tiles stay in that L2).  Fused call: row-major, so that the
+  // workgroups running side by side in one XCD update adjacent column tiles and the 128-byte
+  // lines of master/m/v that straddle a tile border meet in one L2 (218 us against 226 us).
+  q.group_m = mode == EMIT_ADAMW ? 1 : 8;
   q.stagger = mode == EMIT_ADAMW ? kStaggerAdamW : 0;
   const int grid = (q.n_tile_items + 7) / 8 * 8;
   if constexpr (C::WM == 1) {           // this tile is built for the fused call only
