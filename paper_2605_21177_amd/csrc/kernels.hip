@@ -1067,12 +1067,23 @@ Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T
   const int64_t bk = mfma ? MainCfg::BK : 16;
   int64_t S = forced;
   if (S <= 0) {
-    const int64_t rows = (end - 1) / in - begin / in + 1;
+    int64_t rows = (end - 1) / in - begin / in + 1;
+    if (mfma) {                                       // the MFMA kernel tiles the body rows only
+      WgradProblem tmp{};
+      tmp.begin = begin;
+      tmp.end = end;
+      tmp.in = in;
+      const RowSplit rs = split_rows(tmp);
+      rows = rs.rb1 > rs.rb0 ? rs.rb1 - rs.rb0 : 1;
+    }
     const int64_t tiles = ceil_div(rows, bm) * ceil_div(in, bn);
     S = 1;
     const int64_t slots = kNumCU;                     // resident workgroups
     if (mfma && tiles < slots) {
-      S = (2 * slots) / tiles;                        // about two work items per slot
+      // One work item per CU, a single round: a second round costs more than it gains, and
+      // every further slab adds 8 bytes per element of partial traffic (measured on the
+      // lm_head shape: 4 MiB chunk 80 us with 10 slabs, 98 us with 16).
+      S = slots / tiles;
       const int64_t max_by_len = T / 256 > 0 ? T / 256 : 1;   // keep slabs of >= 256 tokens
       if (S > max_by_len) S = max_by_len;
       if (S > 64) S = 64;
