@@ -28,6 +28,17 @@ What each function follows:
 * vector_wgrad          -- same equation for a 1-D scale vector (LayerNorm /
                            RMSNorm weight, Algorithm 1 line 8): y = xhat * w
                            gives dw[j] = sum_t dY[t, j] * xhat[t, j].
+* embedding_wgrad       -- same equation for an embedding table (Algorithm 1 line 8
+                           names Embedding among the chunk-aware operators;
+                           Appendix "Limitations" lists the set): y[t] = W[id[t]]
+                           gives dW[r, :] = sum over the tokens with id[t] = r
+                           of dY[t, :] (textbook), restricted to the range.
+* norm_weight_wgrad     -- same equation for the scale vector of RMSNorm /
+                           LayerNorm when the operator normalises its input
+                           itself: y = w * xhat(x), xhat = x * rstd (RMSNorm) or
+                           (x - mean) * rstd (LayerNorm), so
+                           dw[j] = sum_t dY[t, j] * xhat[t, j] (textbook; the
+                           paper names the operators without formulas).
 * adamw_step            -- Algorithm 1 lines 19-21 (the AdamW update), in that order, fp64.
 * round_to_bf16         -- round-to-nearest-even onto the bfloat16 grid (the
                            paper keeps low-precision parameters beside fp32
@@ -57,6 +68,9 @@ _ELEMENT_SIZE = {F32: 4, BF16: 2}
 
 LINEAR = 0
 VECTOR = 1
+EMBEDDING = 2
+RMSNORM = 3
+LAYERNORM = 4
 
 # bytes of training state per element besides the parameter itself:
 # fp32 gradient + fp32 master + fp32 m + fp32 v (Section 3.3: 4+4+4+4).
@@ -215,6 +229,40 @@ def vector_wgrad(Xhat: np.ndarray, dY: np.ndarray, begin: int, end: int) -> np.n
         raise ValueError("range outside the vector")
     full = np.sum(np.asarray(dY, dtype=np.float64) * np.asarray(Xhat, dtype=np.float64), axis=0)
     return full[begin:end].copy()
+
+
+def embedding_wgrad(ids: np.ndarray, dY: np.ndarray, vocab: int, begin: int, end: int) -> np.ndarray:
+    """Gradient of flat elements [begin, end) of an embedding table W [vocab, dim]
+    whose forward is y[t] = W[ids[t]]: the dense table gradient, formed row by
+    row in token order, then the slice."""
+    ids = np.asarray(ids, dtype=np.int64)
+    dY64 = np.asarray(dY, dtype=np.float64)
+    if dY64.ndim != 2 or ids.shape != (dY64.shape[0],):
+        raise ValueError("ids must be [T] and dY [T, dim]")
+    if ids.size and (ids.min() < 0 or ids.max() >= vocab):
+        raise ValueError("token id outside the table")
+    dim = dY64.shape[1]
+    if not (0 <= begin < end <= vocab * dim):
+        raise ValueError("range outside the tensor")
+    dW = np.zeros((vocab, dim), dtype=np.float64)
+    for t in range(ids.shape[0]):
+        dW[ids[t]] += dY64[t]
+    return dW.reshape(-1)[begin:end].copy()
+
+
+def norm_xhat(x: np.ndarray, eps: float, subtract_mean: bool) -> np.ndarray:
+    """Normalised input of RMSNorm (subtract_mean=False: x / sqrt(mean(x^2) + eps))
+    or LayerNorm (True: (x - mean) / sqrt(var + eps), biased variance), per token."""
+    x64 = np.asarray(x, dtype=np.float64)
+    if subtract_mean:
+        x64 = x64 - x64.mean(axis=1, keepdims=True)
+    return x64 / np.sqrt((x64 * x64).mean(axis=1, keepdims=True) + eps)
+
+
+def norm_weight_wgrad(x: np.ndarray, dY: np.ndarray, eps: float, subtract_mean: bool,
+                      begin: int, end: int) -> np.ndarray:
+    """dw[j] = sum_t dY[t, j] * xhat[t, j] for j in [begin, end), xhat formed from x itself."""
+    return vector_wgrad(norm_xhat(x, eps, subtract_mean), dY, begin, end)
 
 
 # --------------------------------------------------------------------------

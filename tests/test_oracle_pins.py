@@ -395,3 +395,80 @@ def test_cycle_equals_one_dense_update():
         for t in range(len(tensors)):
             assert np.array_equal(only0[t][~touched[t]], params[t][~touched[t]])
             assert np.all(only0[t][touched[t]] != params[t][touched[t]])
+
+
+# ---------------------------------------------------------------- embedding / norms
+def test_embedding_wgrad_bruteforce_and_one_hot_identity():
+    rng = np.random.default_rng(31)
+    vocab, dim, T = 7, 5, 19
+    ids = rng.integers(0, vocab, size=T)
+    dY = rng.standard_normal((T, dim))
+    # brute force: one element at a time
+    dense = np.zeros((vocab, dim))
+    for r in range(vocab):
+        for c in range(dim):
+            for t in range(T):
+                if ids[t] == r:
+                    dense[r, c] += dY[t, c]
+    flat = dense.reshape(-1)
+    for begin, end in ((0, vocab * dim), (3, 4), (6, 23), (5, 10), (30, 35)):
+        np.testing.assert_allclose(O.embedding_wgrad(ids, dY, vocab, begin, end), flat[begin:end], rtol=0, atol=1e-13)
+    # an embedding lookup is a linear layer on one-hot inputs: dW = onehot^T dY
+    onehot = np.zeros((T, vocab))
+    onehot[np.arange(T), ids] = 1.0
+    np.testing.assert_allclose(O.dense_wgrad(dY, onehot), dense, rtol=0, atol=1e-13)
+    # rows that no token names stay zero; a table hit once returns that token's row
+    ids2 = np.array([4, 1])
+    out = O.embedding_wgrad(ids2, dY[:2], vocab, 0, vocab * dim).reshape(vocab, dim)
+    assert np.array_equal(out[4], dY[0]) and np.array_equal(out[1], dY[1]) and not out[[0, 2, 3, 5, 6]].any()
+    # every token names the same row: that row is the column sum
+    out = O.embedding_wgrad(np.full(T, 2), dY, vocab, 2 * dim, 3 * dim)
+    np.testing.assert_allclose(out, dY.sum(axis=0), rtol=0, atol=1e-13)
+    with pytest.raises(ValueError):
+        O.embedding_wgrad(np.array([7]), dY[:1], vocab, 0, 1)
+
+
+def test_embedding_wgrad_against_library_autograd():
+    rng = np.random.default_rng(32)
+    vocab, dim, T = 11, 6, 40
+    ids = rng.integers(0, vocab, size=T)
+    dY = rng.standard_normal((T, dim))
+    W = torch.zeros(vocab, dim, dtype=torch.float64, requires_grad=True)
+    y = torch.nn.functional.embedding(torch.from_numpy(ids), W)
+    (y * torch.from_numpy(dY)).sum().backward()
+    ref = W.grad.numpy().reshape(-1)
+    np.testing.assert_allclose(O.embedding_wgrad(ids, dY, vocab, 0, vocab * dim), ref, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(O.embedding_wgrad(ids, dY, vocab, 13, 47), ref[13:47], rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("subtract_mean", [False, True])
+def test_norm_weight_wgrad_against_library_autograd_and_closed_forms(subtract_mean):
+    rng = np.random.default_rng(33)
+    T, n, eps = 9, 12, 1e-5
+    x = rng.standard_normal((T, n)) * 3.0 + (1.5 if subtract_mean else 0.0)
+    dY = rng.standard_normal((T, n))
+    w = torch.ones(n, dtype=torch.float64, requires_grad=True)
+    xt = torch.from_numpy(x)
+    if subtract_mean:
+        y = torch.nn.functional.layer_norm(xt, (n,), weight=w, bias=None, eps=eps)
+    else:
+        y = xt * torch.rsqrt((xt * xt).mean(dim=1, keepdim=True) + eps) * w
+    (y * torch.from_numpy(dY)).sum().backward()
+    ref = w.grad.numpy()
+    np.testing.assert_allclose(O.norm_weight_wgrad(x, dY, eps, subtract_mean, 0, n), ref, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(O.norm_weight_wgrad(x, dY, eps, subtract_mean, 3, 8), ref[3:8], rtol=1e-12, atol=1e-13)
+    # brute force of the definition for one element
+    j = 5
+    acc = 0.0
+    for t in range(T):
+        row = x[t] - (x[t].mean() if subtract_mean else 0.0)
+        acc += dY[t, j] * row[j] / np.sqrt(np.mean(row * row) + eps)
+    assert abs(O.norm_weight_wgrad(x, dY, eps, subtract_mean, j, j + 1)[0] - acc) < 1e-12
+    # scale invariance: with eps = 0 the normalised input does not change when x is scaled
+    a = O.norm_xhat(x, 0.0, subtract_mean)
+    b = O.norm_xhat(7.0 * x, 0.0, subtract_mean)
+    np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-13)
+    # its rows have unit mean square (and zero mean for LayerNorm)
+    np.testing.assert_allclose((a * a).mean(axis=1), 1.0, rtol=1e-12)
+    if subtract_mean:
+        np.testing.assert_allclose(a.mean(axis=1), 0.0, atol=1e-13)
