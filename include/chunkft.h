@@ -54,9 +54,18 @@ typedef enum {
 
 typedef enum { CHUNKFT_F32 = 0, CHUNKFT_BF16 = 1 } chunkft_dtype;
 
-/* LINEAR: a weight matrix.  VECTOR: a 1-D scale vector (LayerNorm / RMSNorm
- * weight), described as rows = 1, cols = length. */
-typedef enum { CHUNKFT_LINEAR = 0, CHUNKFT_VECTOR = 1 } chunkft_kind;
+/* The chunk-aware backward operators (Algorithm 1 line 8 and the paper's list of
+ * supported modules: Linear, Embedding, LayerNorm, RMSNorm).
+ *   LINEAR     a weight matrix of y = x W^T.
+ *   VECTOR     a 1-D scale vector whose NORMALISED input the caller supplies
+ *              (rows = 1, cols = length).
+ *   EMBEDDING  a lookup table y[t] = W[ids[t]] of rows x cols.
+ *   RMSNORM    the scale vector of y = w * x / sqrt(mean(x^2) + eps); the operator
+ *   LAYERNORM  the scale vector of y = w * (x - mean) / sqrt(var + eps) + b;
+ *              both normalise the raw input themselves (rows = 1). */
+typedef enum {
+  CHUNKFT_LINEAR = 0, CHUNKFT_VECTOR = 1, CHUNKFT_EMBEDDING = 2, CHUNKFT_RMSNORM = 3, CHUNKFT_LAYERNORM = 4
+} chunkft_kind;
 
 /* ------------------------------------------------------------------------
  * Cycle planner (host only)
@@ -122,16 +131,23 @@ int chunkft_plan_cycle(const chunkft_tensor_desc* tensors, int32_t n_tensors,
 typedef struct {
   int32_t kind;      /* chunkft_kind */
   int32_t dtype;     /* chunkft_dtype of X, dY (and of W in the fused call) */
-  int64_t out, in;   /* W shape; VECTOR: out = 1, in = vector length */
+  int64_t out, in;   /* W shape; the 1-D kinds: out = 1, in = vector length;
+                        EMBEDDING: out = table rows, in = embedding width */
   int64_t T;         /* tokens */
   const void* X;     /* (device) LINEAR: [T, in] layer input.  VECTOR: [T, in] the
-                        normalised activations that the scale multiplies */
-  int64_t ldx;       /* row stride of X in elements, >= in */
-  const void* dY;    /* (device) LINEAR: [T, out] output gradient.  VECTOR: [T, in] */
+                        normalised activations that the scale multiplies.
+                        RMSNORM / LAYERNORM: [T, in] the operator's raw input.
+                        EMBEDDING: T token ids as int64 (ids outside the table
+                        rows of the range are ignored) */
+  int64_t ldx;       /* row stride of X in elements, >= in (EMBEDDING: ignored) */
+  const void* dY;    /* (device) LINEAR: [T, out] output gradient.  Others: [T, in] */
   int64_t lddy;      /* row stride of dY in elements */
   int32_t split_k;   /* 0: the library picks the number of token slabs S from the
-                        shape alone; 1..64: use exactly this S */
+                        shape alone; 1..64: use exactly this S (LINEAR only;
+                        the other kinds always use one slab) */
   int32_t reserved;  /* must be 0 */
+  double norm_eps;   /* RMSNORM / LAYERNORM: the eps under the square root, >= 0;
+                        other kinds: ignored */
 } chunkft_layer;
 
 /* Number of token slabs S the two wgrad entry points will use for this call
@@ -140,7 +156,8 @@ typedef struct {
 int chunkft_split_k(const chunkft_layer* L, int64_t begin, int64_t end);
 
 /* Bytes of device workspace the two wgrad entry points need for this call:
- * 0 when S = 1, else S * (end - begin) * 4 for the per-slab partial sums.
+ * LINEAR: 0 when S = 1, else S * (end - begin) * 4 for the per-slab partial sums;
+ * RMSNORM / LAYERNORM: 8 * T for the per-token statistics; other kinds 0.
  * Returns 0 also for invalid arguments (the call itself reports those). */
 size_t chunkft_workspace_bytes(const chunkft_layer* L, int64_t begin, int64_t end);
 
@@ -150,8 +167,16 @@ size_t chunkft_workspace_bytes(const chunkft_layer* L, int64_t begin, int64_t en
  * Paper: Section 3.1, equation g^(k) = grad_{theta^(k)} L -- the backward pass
  * produces the gradient of the active slices only, into an auxiliary fp32
  * buffer, never a dense gradient (also Algorithm 1 line 18).  For y = x W^T:
- *   LINEAR  g[i] = sum_t dY[t, r] * X[t, c],  begin + i = r * in + c
- *   VECTOR  g[i] = sum_t dY[t, j] * X[t, j],  j = begin + i
+ *   LINEAR     g[i] = sum_t dY[t, r] * X[t, c],  begin + i = r * in + c
+ *   VECTOR     g[i] = sum_t dY[t, j] * X[t, j],  j = begin + i
+ *   EMBEDDING  g[i] = sum over the tokens t with ids[t] = r of dY[t, c], in
+ *              ascending token order (no atomics: the result is reproducible)
+ *   RMSNORM    g[i] = sum_t dY[t, j] * X[t, j] * rstd[t],
+ *              rstd[t] = 1 / sqrt(mean_j X[t, j]^2 + eps)
+ *   LAYERNORM  g[i] = sum_t dY[t, j] * (X[t, j] - mean[t]) * rstd[t],
+ *              rstd[t] = 1 / sqrt(var[t] + eps), biased variance
+ * (the paper names the last three operators without formulas; these are the
+ * textbook gradients of the forms given with chunkft_kind).
  * Products and sums are fp32 (bf16 inputs are multiplied exactly); the sum
  * over tokens is taken slab by slab in a fixed order.
  *

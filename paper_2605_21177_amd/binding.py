@@ -28,6 +28,9 @@ F32 = 0
 BF16 = 1
 LINEAR = 0
 VECTOR = 1
+EMBEDDING = 2
+RMSNORM = 3
+LAYERNORM = 4
 
 PLAN_GREEDY = 0
 PLAN_TRAINING_COST = 1
@@ -56,7 +59,8 @@ class AdamWHparams(C.Structure):
 class Layer(C.Structure):
     _fields_ = [("kind", C.c_int32), ("dtype", C.c_int32), ("out", C.c_int64), ("n_in", C.c_int64),
                 ("T", C.c_int64), ("X", C.c_void_p), ("ldx", C.c_int64), ("dY", C.c_void_p),
-                ("lddy", C.c_int64), ("split_k", C.c_int32), ("reserved", C.c_int32)]
+                ("lddy", C.c_int64), ("split_k", C.c_int32), ("reserved", C.c_int32),
+                ("norm_eps", C.c_double)]
 
 
 class ChunkFTError(RuntimeError):
@@ -160,17 +164,25 @@ def _torch_dtype_code(t) -> int:
     raise TypeError(f"unsupported tensor dtype {t.dtype}")
 
 
-def make_layer(kind: int, X, dY, out: int, n_in: int, split_k: int = 0) -> Layer:
-    """Describe a backward step from two row-major 2-D device tensors."""
-    if X.dim() != 2 or dY.dim() != 2 or X.stride(1) != 1 or dY.stride(1) != 1:
-        raise ValueError("X and dY must be 2-D with unit inner stride")
+def make_layer(kind: int, X, dY, out: int, n_in: int, split_k: int = 0, norm_eps: float = 0.0) -> Layer:
+    """Describe a backward step from two row-major device tensors: X [T, in] and dY
+    (for EMBEDDING X is the 1-D int64 tensor of token ids)."""
+    if dY.dim() != 2 or dY.stride(1) != 1:
+        raise ValueError("dY must be 2-D with unit inner stride")
     if not (X.is_cuda and dY.is_cuda):
         raise ValueError("X and dY must live on the GPU")
-    d = _torch_dtype_code(X)
-    if _torch_dtype_code(dY) != d:
+    d = _torch_dtype_code(dY)
+    if kind == EMBEDDING:
+        import torch
+        if X.dim() != 1 or X.dtype != torch.int64 or X.stride(0) != 1 or X.shape[0] != dY.shape[0]:
+            raise ValueError("token ids must be a contiguous 1-D int64 tensor with one id per row of dY")
+        return Layer(kind, d, out, n_in, X.shape[0], X.data_ptr(), 1, dY.data_ptr(), dY.stride(0), split_k, 0, 0.0)
+    if X.dim() != 2 or X.stride(1) != 1:
+        raise ValueError("X must be 2-D with unit inner stride")
+    if _torch_dtype_code(X) != d:
         raise TypeError("X and dY must share a dtype")
     return Layer(kind, d, out, n_in, X.shape[0], X.data_ptr(), X.stride(0), dY.data_ptr(), dY.stride(0),
-                 split_k, 0)
+                 split_k, 0, float(norm_eps))
 
 
 def _stream_ptr(stream) -> int:

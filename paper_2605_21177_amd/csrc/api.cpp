@@ -26,22 +26,27 @@ Checked check_layer(const chunkft_layer* L, int64_t begin, int64_t end) {
   Checked c{};
   c.status = CHUNKFT_ERR_INVALID_ARG;
   if (!L) return c;
-  if (L->kind != CHUNKFT_LINEAR && L->kind != CHUNKFT_VECTOR) { c.status = CHUNKFT_ERR_DTYPE; return c; }
+  if (L->kind < CHUNKFT_LINEAR || L->kind > CHUNKFT_LAYERNORM) { c.status = CHUNKFT_ERR_DTYPE; return c; }
+  const bool one_d = L->kind == CHUNKFT_VECTOR || L->kind == CHUNKFT_RMSNORM || L->kind == CHUNKFT_LAYERNORM;
+  const bool norm = L->kind == CHUNKFT_RMSNORM || L->kind == CHUNKFT_LAYERNORM;
+  const bool embed = L->kind == CHUNKFT_EMBEDDING;
   if (L->dtype != CHUNKFT_F32 && L->dtype != CHUNKFT_BF16) { c.status = CHUNKFT_ERR_DTYPE; return c; }
   if (!L->X || !L->dY) return c;
   if (L->out <= 0 || L->in <= 0 || L->T <= 0) return c;
   if (L->reserved != 0) return c;
   if (L->split_k < 0 || L->split_k > 64) return c;
-  if (L->kind == CHUNKFT_VECTOR && L->out != 1) return c;
-  if (L->ldx < L->in) return c;
+  if (one_d && L->out != 1) return c;
+  if (L->kind != CHUNKFT_LINEAR && L->split_k > 1) return c;
+  if (norm && !(L->norm_eps >= 0.0 && std::isfinite(L->norm_eps))) return c;
+  if (!embed && L->ldx < L->in) return c;
   if (L->lddy < (L->kind == CHUNKFT_LINEAR ? L->out : L->in)) return c;
   if (L->in > kMaxI64 / L->out) { c.status = CHUNKFT_ERR_OVERFLOW; return c; }
   // element offsets t * ld + column must stay inside int64
-  if (L->ldx > kMaxI64 / L->T || L->lddy > kMaxI64 / L->T) { c.status = CHUNKFT_ERR_OVERFLOW; return c; }
+  if ((!embed && L->ldx > kMaxI64 / L->T) || L->lddy > kMaxI64 / L->T) { c.status = CHUNKFT_ERR_OVERFLOW; return c; }
   const int64_t numel = L->out * L->in;
   if (begin < 0 || begin >= end || end > numel) { c.status = CHUNKFT_ERR_RANGE; return c; }
   const uintptr_t esz = L->dtype == CHUNKFT_F32 ? 4 : 2;
-  if ((reinterpret_cast<uintptr_t>(L->X) % esz) || (reinterpret_cast<uintptr_t>(L->dY) % esz)) return c;
+  if ((reinterpret_cast<uintptr_t>(L->X) % (embed ? 8 : esz)) || (reinterpret_cast<uintptr_t>(L->dY) % esz)) return c;
 
   WgradProblem& p = c.p;
   p.X = L->X;
@@ -81,9 +86,15 @@ int check_hparams(const chunkft_adamw_hparams* hp, AdamWConsts* out) {
   return CHUNKFT_OK;
 }
 
-int check_workspace(const WgradProblem& p, void* ws, size_t ws_bytes) {
-  if (p.S <= 1) return CHUNKFT_OK;
-  const size_t need = static_cast<size_t>(p.S) * static_cast<size_t>(p.end - p.begin) * 4u;
+size_t workspace_need(const chunkft_layer* L, const WgradProblem& p) {
+  if (L->kind == CHUNKFT_RMSNORM || L->kind == CHUNKFT_LAYERNORM) return static_cast<size_t>(p.T) * 8u;
+  if (p.S <= 1) return 0;
+  return static_cast<size_t>(p.S) * static_cast<size_t>(p.end - p.begin) * 4u;
+}
+
+int check_workspace(const chunkft_layer* L, const WgradProblem& p, void* ws, size_t ws_bytes) {
+  const size_t need = workspace_need(L, p);
+  if (need == 0) return CHUNKFT_OK;
   if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 15u)) return CHUNKFT_ERR_WORKSPACE;
   return CHUNKFT_OK;
 }
@@ -91,6 +102,10 @@ int check_workspace(const WgradProblem& p, void* ws, size_t ws_bytes) {
 int run_wgrad(const chunkft_layer* L, const Checked& c, int mode, const Sinks& s, void* stream) {
   int e;
   if (L->kind == CHUNKFT_VECTOR) e = launch_colsum(c.p, L->dtype, mode, s, stream);
+  else if (L->kind == CHUNKFT_EMBEDDING) e = launch_embed_wgrad(c.p, L->dtype, mode, s, stream);
+  else if (L->kind == CHUNKFT_RMSNORM || L->kind == CHUNKFT_LAYERNORM)
+    e = launch_norm_wgrad(c.p, L->dtype, L->kind == CHUNKFT_LAYERNORM, static_cast<float>(L->norm_eps), s.ws,
+                          mode, s, stream);
   else if (c.mfma) e = launch_wgrad_bf16_mfma(c.p, mode, s, stream);
   else e = launch_wgrad_simt(c.p, L->dtype, mode, s, stream);
   return e == 0 ? CHUNKFT_OK : CHUNKFT_ERR_HIP;
@@ -105,8 +120,8 @@ extern "C" int chunkft_split_k(const chunkft_layer* L, int64_t begin, int64_t en
 
 extern "C" size_t chunkft_workspace_bytes(const chunkft_layer* L, int64_t begin, int64_t end) {
   const Checked c = check_layer(L, begin, end);
-  if (c.status != CHUNKFT_OK || c.p.S <= 1) return 0;
-  return static_cast<size_t>(c.p.S) * static_cast<size_t>(end - begin) * 4u;
+  if (c.status != CHUNKFT_OK) return 0;
+  return workspace_need(L, c.p);
 }
 
 extern "C" int chunkft_chunk_wgrad(const chunkft_layer* L, int64_t begin, int64_t end, float* g,
@@ -115,7 +130,7 @@ extern "C" int chunkft_chunk_wgrad(const chunkft_layer* L, int64_t begin, int64_
   if (c.status != CHUNKFT_OK) return c.status;
   if (!g || (reinterpret_cast<uintptr_t>(g) & 3u)) return CHUNKFT_ERR_INVALID_ARG;
   if (accumulate != 0 && accumulate != 1) return CHUNKFT_ERR_INVALID_ARG;
-  const int wsr = check_workspace(c.p, ws, ws_bytes);
+  const int wsr = check_workspace(L, c.p, ws, ws_bytes);
   if (wsr != CHUNKFT_OK) return wsr;
   Sinks s{};
   s.g = g;
@@ -164,7 +179,7 @@ extern "C" int chunkft_wgrad_adamw_fused(const chunkft_layer* L, int64_t begin, 
   Sinks s{};
   const int hr = check_hparams(hp, &s.c);
   if (hr != CHUNKFT_OK) return hr;
-  const int wsr = check_workspace(c.p, ws, ws_bytes);
+  const int wsr = check_workspace(L, c.p, ws, ws_bytes);
   if (wsr != CHUNKFT_OK) return wsr;
   s.master = master;
   s.m = m;

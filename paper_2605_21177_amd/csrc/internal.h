@@ -63,6 +63,12 @@ Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T
 int launch_wgrad_bf16_mfma(const WgradProblem& p, int mode, const Sinks& s, void* stream);
 int launch_wgrad_simt(const WgradProblem& p, int dtype, int mode, const Sinks& s, void* stream);
 int launch_colsum(const WgradProblem& p, int dtype, int mode, const Sinks& s, void* stream);
+// Scale vector of RMSNorm / LayerNorm with the normalisation done here: p.X is the raw input,
+// stats is a device scratch of 2 * T floats.
+int launch_norm_wgrad(const WgradProblem& p, int dtype, bool subtract_mean, float eps, float* stats, int mode,
+                      const Sinks& s, void* stream);
+// Embedding table: p.X holds the int64 token ids, p.dY is [T, in], the table is [out, in].
+int launch_embed_wgrad(const WgradProblem& p, int dtype, int mode, const Sinks& s, void* stream);
 // g = sum over slabs (EMIT_STORE / EMIT_ACCUM) or AdamW on that sum (EMIT_ADAMW).
 // W_at_begin is already offset to the first element.
 int launch_reduce(const float* ws, int32_t S, int64_t E, int mode, const Sinks& s, void* W_at_begin,

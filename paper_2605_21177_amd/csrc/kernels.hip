@@ -888,8 +888,10 @@ __global__ __launch_bounds__(256) void wgrad_simt_kernel(const SimtParams q) {
 // ---------------------------------------------------------------------------
 // scale-vector gradient: g[j] = sum_t dY[t, j] * X[t, j]
 // ---------------------------------------------------------------------------
-template <typename T, int MODE>
-__global__ __launch_bounds__(1024) void colsum_kernel(const WgradProblem p, const Sinks s) {
+// With NORM the operator normalises its input itself: X is the raw input and stats[2t],
+// stats[2t+1] are the token's mean (0 for RMSNorm) and reciprocal standard deviation.
+template <typename T, int MODE, int NORM>
+__global__ __launch_bounds__(1024) void colsum_kernel(const WgradProblem p, const Sinks s, const float* stats) {
   constexpr int TG = 16;
   __shared__ float red[TG][64];
   const int lane = threadIdx.x & 63, tg = threadIdx.x >> 6;
@@ -898,14 +900,141 @@ __global__ __launch_bounds__(1024) void colsum_kernel(const WgradProblem p, cons
   const T* X = (const T*)p.X;
   float acc = 0.f;
   if (j < p.end)
-    for (int64_t t = tg; t < p.T; t += TG)
-      acc = fmaf(load_as_f32<T>(dY + t * p.lddy + j), load_as_f32<T>(X + t * p.ldx + j), acc);
+    for (int64_t t = tg; t < p.T; t += TG) {
+      float x = load_as_f32<T>(X + t * p.ldx + j);
+      if constexpr (NORM) x = (x - stats[2 * t]) * stats[2 * t + 1];
+      acc = fmaf(load_as_f32<T>(dY + t * p.lddy + j), x, acc);
+    }
   red[tg][lane] = acc;
   __syncthreads();
   if (tg == 0 && j < p.end) {
     float sum = red[0][lane];
     for (int g = 1; g < TG; ++g) sum += red[g][lane];
     emit<MODE>(s, p.end - p.begin, 0, j - p.begin, j, sum);
+  }
+}
+
+// Per-token statistics of RMSNorm (SUB = 0) or LayerNorm (SUB = 1): one wave per token, two
+// passes over the row (mean first, then the centred sum of squares), fp32.
+template <typename T, int SUB>
+__global__ __launch_bounds__(256) void norm_stats_kernel(const T* X, int64_t ldx, int64_t n, int64_t tokens,
+                                                         float eps, float* stats) {
+  const int lane = threadIdx.x & 63;
+  const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= tokens) return;
+  const T* row = X + t * ldx;
+  auto wave_sum = [](float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+  };
+  float mean = 0.f;
+  if constexpr (SUB) {
+    float s1 = 0.f;
+    for (int64_t j = lane; j < n; j += 64) s1 += load_as_f32<T>(row + j);
+    mean = wave_sum(s1) / (float)n;
+  }
+  float s2 = 0.f;
+  for (int64_t j = lane; j < n; j += 64) {
+    const float d = load_as_f32<T>(row + j) - mean;
+    s2 = fmaf(d, d, s2);
+  }
+  const float var = wave_sum(s2) / (float)n;
+  if (lane == 0) {
+    stats[2 * t] = mean;
+    stats[2 * t + 1] = 1.0f / sqrtf(var + eps);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// embedding table gradient: g[r, :] = sum over the tokens t with ids[t] = r of dY[t, :]
+// ---------------------------------------------------------------------------
+// One wave per table row of the chunk, kEmbRows rows per workgroup.  A wave walks the token
+// ids 64 at a time, keeps those that name its row (ballot) and adds their dY rows in
+// ascending token order: no atomics, the order of the sum is fixed.  A lane holds the
+// columns 256 i + 4 lane + e (i < kEmbIter, e < 4) of the block of 256 kEmbIter columns the
+// workgroup covers (blockIdx.y), so loads and stores of a wave are 1 KB (fp32) pieces.
+// HBM-bound: the rows are written (or updated) once, whether any token names them or not.
+constexpr int kEmbRows = 4;
+constexpr int kEmbIter = 8;
+
+template <typename T> __device__ __forceinline__ void load4_as_f32(const T* p, int valid, float (&o)[4]);
+template <> __device__ __forceinline__ void load4_as_f32<float>(const float* p, int valid, float (&o)[4]) {
+  if (valid >= 4) {
+    const f32x4_u v = *(const f32x4_u*)p;
+    o[0] = v[0]; o[1] = v[1]; o[2] = v[2]; o[3] = v[3];
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = e < valid ? p[e] : 0.f;
+  }
+}
+template <> __device__ __forceinline__ void load4_as_f32<unsigned short>(const unsigned short* p, int valid,
+                                                                         float (&o)[4]) {
+  if (valid >= 4) {
+    const u32x2_a2 v = *(const u32x2_a2*)p;
+    o[0] = __uint_as_float(v[0] << 16); o[1] = __uint_as_float(v[0] & 0xffff0000u);
+    o[2] = __uint_as_float(v[1] << 16); o[3] = __uint_as_float(v[1] & 0xffff0000u);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = e < valid ? bf16_bits_to_f32(p[e]) : 0.f;
+  }
+}
+
+template <typename T, int MODE>
+__global__ __launch_bounds__(64 * kEmbRows) void embed_wgrad_kernel(const WgradProblem p, const Sinks s) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row = p.begin / p.in + (int64_t)blockIdx.x * kEmbRows + wave;
+  if (row > (p.end - 1) / p.in) return;           // no barrier below: a wave may leave alone
+  const int64_t cbase = (int64_t)blockIdx.y * (256 * kEmbIter);
+  const int64_t* ids = (const int64_t*)p.X;
+  const T* dY = (const T*)p.dY;
+  float acc[kEmbIter][4];
+#pragma unroll
+  for (int i = 0; i < kEmbIter; ++i)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[i][e] = 0.f;
+  for (int64_t t0 = 0; t0 < p.T; t0 += 64) {
+    const int64_t t = t0 + lane;
+    unsigned long long hits = __ballot(t < p.T && ids[t] == row);
+    while (hits) {
+      const int b = __ffsll((long long)hits) - 1;
+      hits &= hits - 1;
+      const T* src = dY + (t0 + b) * p.lddy;
+#pragma unroll
+      for (int i = 0; i < kEmbIter; ++i) {
+        const int64_t c = cbase + i * 256 + 4 * lane;
+        if (c < p.in) {
+          float x[4];
+          load4_as_f32<T>(src + c, (int)(p.in - c < 4 ? p.in - c : 4), x);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[i][e] += x[e];
+        }
+      }
+    }
+  }
+  const int64_t E = p.end - p.begin;
+#pragma unroll
+  for (int i = 0; i < kEmbIter; ++i) {
+    const int64_t c = cbase + i * 256 + 4 * lane;
+    if (c >= p.in) continue;
+    const int64_t flat = row * p.in + c;
+    if (flat >= p.begin && flat + 4 <= p.end && c + 4 <= p.in) {
+      const int64_t k = flat - p.begin;
+      Vec4Sink d;
+      d.g = s.g + k;
+      d.master = s.master + k;
+      d.m = s.m + k;
+      d.v = s.v + k;
+      d.W = s.w_kind == W_BF16 ? (void*)((unsigned short*)s.W + flat) : (void*)((float*)s.W + flat);
+      const State4 st = load_state4<MODE>(d);
+      const f32x4_u val = {acc[i][0], acc[i][1], acc[i][2], acc[i][3]};
+      finish4<MODE>(d, s.w_kind, s.c, val, st);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (c + e < p.in && flat + e >= p.begin && flat + e < p.end)
+          emit<MODE>(s, E, 0, flat + e - p.begin, flat + e, acc[i][e]);
+    }
   }
 }
 
@@ -1184,12 +1313,13 @@ int launch_wgrad_simt(const WgradProblem& p, int dtype, int mode, const Sinks& s
                     : launch_simt_t<unsigned short>(q, (int)grid, mode, st);
 }
 
-template <typename T>
-static int launch_colsum_t(const WgradProblem& p, int grid, int mode, const Sinks& s, hipStream_t st) {
+template <typename T, int NORM>
+static int launch_colsum_t(const WgradProblem& p, int grid, int mode, const Sinks& s, const float* stats,
+                           hipStream_t st) {
   switch (mode) {
-    case EMIT_STORE: hipLaunchKernelGGL((colsum_kernel<T, EMIT_STORE>), dim3(grid), dim3(1024), 0, st, p, s); break;
-    case EMIT_ACCUM: hipLaunchKernelGGL((colsum_kernel<T, EMIT_ACCUM>), dim3(grid), dim3(1024), 0, st, p, s); break;
-    default: hipLaunchKernelGGL((colsum_kernel<T, EMIT_ADAMW>), dim3(grid), dim3(1024), 0, st, p, s); break;
+    case EMIT_STORE: hipLaunchKernelGGL((colsum_kernel<T, EMIT_STORE, NORM>), dim3(grid), dim3(1024), 0, st, p, s, stats); break;
+    case EMIT_ACCUM: hipLaunchKernelGGL((colsum_kernel<T, EMIT_ACCUM, NORM>), dim3(grid), dim3(1024), 0, st, p, s, stats); break;
+    default: hipLaunchKernelGGL((colsum_kernel<T, EMIT_ADAMW, NORM>), dim3(grid), dim3(1024), 0, st, p, s, stats); break;
   }
   return (int)hipGetLastError();
 }
@@ -1198,8 +1328,45 @@ int launch_colsum(const WgradProblem& p, int dtype, int mode, const Sinks& s, vo
   const int64_t grid = ceil_div(p.end - p.begin, 64);
   if (grid > 0x7fffffff) return (int)hipErrorInvalidValue;
   hipStream_t st = (hipStream_t)stream;
-  return dtype == 0 ? launch_colsum_t<float>(p, (int)grid, mode, s, st)
-                    : launch_colsum_t<unsigned short>(p, (int)grid, mode, s, st);
+  return dtype == 0 ? launch_colsum_t<float, 0>(p, (int)grid, mode, s, nullptr, st)
+                    : launch_colsum_t<unsigned short, 0>(p, (int)grid, mode, s, nullptr, st);
+}
+
+int launch_norm_wgrad(const WgradProblem& p, int dtype, bool subtract_mean, float eps, float* stats, int mode,
+                      const Sinks& s, void* stream) {
+  const int64_t grid = ceil_div(p.end - p.begin, 64), sgrid = ceil_div(p.T, 4);
+  if (grid > 0x7fffffff || sgrid > 0x7fffffff) return (int)hipErrorInvalidValue;
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == 0) {
+    if (subtract_mean) hipLaunchKernelGGL((norm_stats_kernel<float, 1>), dim3((int)sgrid), dim3(256), 0, st, (const float*)p.X, p.ldx, p.in, p.T, eps, stats);
+    else hipLaunchKernelGGL((norm_stats_kernel<float, 0>), dim3((int)sgrid), dim3(256), 0, st, (const float*)p.X, p.ldx, p.in, p.T, eps, stats);
+  } else {
+    if (subtract_mean) hipLaunchKernelGGL((norm_stats_kernel<unsigned short, 1>), dim3((int)sgrid), dim3(256), 0, st, (const unsigned short*)p.X, p.ldx, p.in, p.T, eps, stats);
+    else hipLaunchKernelGGL((norm_stats_kernel<unsigned short, 0>), dim3((int)sgrid), dim3(256), 0, st, (const unsigned short*)p.X, p.ldx, p.in, p.T, eps, stats);
+  }
+  const int err = (int)hipGetLastError();
+  if (err != 0) return err;
+  return dtype == 0 ? launch_colsum_t<float, 1>(p, (int)grid, mode, s, stats, st)
+                    : launch_colsum_t<unsigned short, 1>(p, (int)grid, mode, s, stats, st);
+}
+
+template <typename T>
+static int launch_embed_t(const WgradProblem& p, dim3 grid, int mode, const Sinks& s, hipStream_t st) {
+  switch (mode) {
+    case EMIT_STORE: hipLaunchKernelGGL((embed_wgrad_kernel<T, EMIT_STORE>), grid, dim3(64 * kEmbRows), 0, st, p, s); break;
+    case EMIT_ACCUM: hipLaunchKernelGGL((embed_wgrad_kernel<T, EMIT_ACCUM>), grid, dim3(64 * kEmbRows), 0, st, p, s); break;
+    default: hipLaunchKernelGGL((embed_wgrad_kernel<T, EMIT_ADAMW>), grid, dim3(64 * kEmbRows), 0, st, p, s); break;
+  }
+  return (int)hipGetLastError();
+}
+
+int launch_embed_wgrad(const WgradProblem& p, int dtype, int mode, const Sinks& s, void* stream) {
+  const int64_t rows = (p.end - 1) / p.in - p.begin / p.in + 1;
+  const int64_t gx = ceil_div(rows, kEmbRows), gy = ceil_div(p.in, 256 * kEmbIter);
+  if (gx > 0x7fffffff || gy > 65535) return (int)hipErrorInvalidValue;
+  const dim3 grid((unsigned)gx, (unsigned)gy);
+  return dtype == 0 ? launch_embed_t<float>(p, grid, mode, s, (hipStream_t)stream)
+                    : launch_embed_t<unsigned short>(p, grid, mode, s, (hipStream_t)stream);
 }
 
 static int launch_elem(ElemParams& q, int mode, hipStream_t st) {

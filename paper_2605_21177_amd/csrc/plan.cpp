@@ -96,7 +96,7 @@ extern "C" int chunkft_plan_cycle(const chunkft_tensor_desc* tensors, int32_t n_
   for (int32_t t = 0; t < n_tensors; ++t) {
     const chunkft_tensor_desc& d = tensors[t];
     if (d.rows < 0 || d.cols < 0) return CHUNKFT_ERR_INVALID_ARG;
-    if (d.kind != CHUNKFT_LINEAR && d.kind != CHUNKFT_VECTOR) return CHUNKFT_ERR_DTYPE;
+    if (d.kind < CHUNKFT_LINEAR || d.kind > CHUNKFT_LAYERNORM) return CHUNKFT_ERR_DTYPE;
     int64_t s;
     if (d.dtype == CHUNKFT_F32) s = 4;
     else if (d.dtype == CHUNKFT_BF16) s = 2;

@@ -34,6 +34,9 @@ F32 = 0
 BF16 = 1
 LINEAR = 0
 VECTOR = 1
+EMBEDDING = 2
+RMSNORM = 3
+LAYERNORM = 4
 
 MiB = 1 << 20
 
@@ -102,9 +105,10 @@ class LayerCase:
     out: int
     n_in: int
     T: int
-    X: torch.Tensor          # [T, in]
-    dY: torch.Tensor         # LINEAR [T, out]; VECTOR [T, in]
-    W0: torch.Tensor         # LINEAR [out, in]; VECTOR [in]; storage dtype
+    X: torch.Tensor          # [T, in]; EMBEDDING: the T token ids (int64)
+    dY: torch.Tensor         # LINEAR [T, out]; others [T, in]
+    W0: torch.Tensor         # LINEAR / EMBEDDING [out, in]; 1-D kinds [in]; storage dtype
+    eps: float = 0.0         # RMSNORM / LAYERNORM
 
     @property
     def numel(self) -> int:
@@ -133,6 +137,35 @@ def vector_case(rng, name, n, T, dtype, sigma_dy) -> LayerCase:
     if dtype == BF16:
         W0 = W0.to(torch.bfloat16)
     return LayerCase(name, VECTOR, dtype, 1, n, T, X, dY, W0)
+
+
+def embedding_case(rng, name, vocab, dim, T, dtype, sigma_dy) -> LayerCase:
+    """Embedding table [vocab, dim] with T token ids whose frequencies are heavy-tailed
+    (rank r drawn with probability ~ 1/(r + 1), ranks scattered over the table), as token
+    counts of text are: a few rows collect many tokens, most rows none."""
+    ranks = np.minimum((np.exp(rng.random(T) * np.log(vocab + 1.0)) - 1.0).astype(np.int64), vocab - 1)
+    perm = rng.permutation(vocab)
+    ids = torch.from_numpy(perm[ranks].astype(np.int64))
+    dY = normal(rng, (T, dim), sigma_dy, dtype)
+    W0 = normal(rng, (vocab, dim), 0.02, dtype)
+    return LayerCase(name, EMBEDDING, dtype, vocab, dim, T, ids, dY, W0)
+
+
+def norm_case(rng, name, n, T, dtype, sigma_dy, kind, eps=1e-5) -> LayerCase:
+    """Scale vector of RMSNorm / LayerNorm: raw activations with a per-token scale and,
+    for LayerNorm, a non-zero mean."""
+    a = rng.standard_normal(size=(T, n), dtype=np.float32)
+    a *= (0.5 + 2.0 * rng.random(T).astype(np.float32))[:, None]
+    if kind == LAYERNORM:
+        a += rng.standard_normal(size=(T, 1), dtype=np.float32)
+    X = torch.from_numpy(a)
+    if dtype == BF16:
+        X = X.to(torch.bfloat16)
+    dY = normal(rng, (T, n), sigma_dy, dtype)
+    W0 = normal(rng, (n,), 0.02, F32) + 1.0
+    if dtype == BF16:
+        W0 = W0.to(torch.bfloat16)
+    return LayerCase(name, kind, dtype, 1, n, T, X, dY, W0, eps)
 
 
 # --------------------------------------------------------------------------

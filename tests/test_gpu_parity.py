@@ -39,11 +39,15 @@ def _state_for(case, begin, end, rng, warm):
 def _full_check(case, begin, end, split_k=None, warm=False, step=1, check_accum=True):
     """wgrad, accumulate, fused (+ fused == un-fused + AdamW bit for bit), W untouched outside."""
     dl = H.DeviceLayer(case)
-    X64, dY64 = WL.as_f64(case.X), WL.as_f64(case.dY)
-    if case.kind == WL.LINEAR:
-        g_ref = O.chunk_wgrad(X64, dY64, begin, end, dense=(case.numel <= (1 << 22)))
+    dY64 = WL.as_f64(case.dY)
+    if case.kind == WL.EMBEDDING:
+        g_ref = O.embedding_wgrad(case.X.numpy(), dY64, case.out, begin, end)
+    elif case.kind == WL.LINEAR:
+        g_ref = O.chunk_wgrad(WL.as_f64(case.X), dY64, begin, end, dense=(case.numel <= (1 << 22)))
+    elif case.kind == WL.VECTOR:
+        g_ref = O.vector_wgrad(WL.as_f64(case.X), dY64, begin, end)
     else:
-        g_ref = O.vector_wgrad(X64, dY64, begin, end)
+        g_ref = O.norm_weight_wgrad(WL.as_f64(case.X), dY64, case.eps, case.kind == WL.LAYERNORM, begin, end)
     n = end - begin
 
     g = H.gpu_wgrad(dl, begin, end, split_k)
@@ -178,6 +182,32 @@ def test_vector_kind():
         case = WL.vector_case(rng, "norm", 1000, 77, dtype, 1e-3)
         for begin, end in ((0, 1000), (3, 997), (500, 501)):
             _full_check(case, begin, end)
+
+
+@pytest.mark.parametrize("dtype", [WL.BF16, WL.F32])
+def test_embedding_kind(dtype):
+    """Table rows hit by many tokens, by one and by none; ranges that start and end mid-row;
+    a width that is not a multiple of 4 (element-wise path) and one wider than a column block."""
+    rng = np.random.default_rng(82)
+    case = WL.embedding_case(rng, "embed", 300, 264, 500, dtype, 1e-3)
+    for begin, end in ((0, 300 * 264), (264 * 7 + 33, 264 * 251 + 5), (264 * 40, 264 * 41), (17, 18)):
+        _full_check(case, begin, end)
+    odd = WL.embedding_case(rng, "embed_odd", 50, 2051, 90, dtype, 1e-3)      # 2051 columns: two blocks, ragged
+    _full_check(odd, 2051 * 3 + 1, 2051 * 44 + 2050)
+    same = WL.embedding_case(rng, "embed_same", 40, 64, 200, dtype, 1e-3)
+    same.X[:] = 11                                                            # every token names row 11
+    _full_check(same, 0, 40 * 64)
+
+
+@pytest.mark.parametrize("kind", [WL.RMSNORM, WL.LAYERNORM])
+def test_self_normalising_scale_vectors(kind):
+    rng = np.random.default_rng(83)
+    for dtype in (WL.BF16, WL.F32):
+        case = WL.norm_case(rng, "norm", 1000, 77, dtype, 1e-3, kind)
+        for begin, end in ((0, 1000), (3, 997), (500, 501)):
+            _full_check(case, begin, end)
+    wide = WL.norm_case(rng, "norm_wide", 4096, 300, WL.BF16, 1e-3, kind, eps=1e-6)
+    _full_check(wide, 0, 4096)
 
 
 def test_warm_state_second_step():

@@ -122,7 +122,7 @@ P = 0x1000
 
 def _layer(**kw):
     d = dict(kind=B.LINEAR, dtype=B.BF16, out=64, n_in=32, T=16, X=P, ldx=32, dY=P, lddy=64, split_k=0,
-             reserved=0)
+             reserved=0, norm_eps=0.0)
     d.update(kw)
     return B.Layer(**d)
 
@@ -136,7 +136,14 @@ def test_device_calls_reject_bad_arguments_without_launching():
         (_layer(ldx=31), 0, 10, B.ERR_INVALID_ARG),
         (_layer(lddy=63), 0, 10, B.ERR_INVALID_ARG),
         (_layer(dtype=7), 0, 10, B.ERR_DTYPE),
-        (_layer(kind=2), 0, 10, B.ERR_DTYPE),
+        (_layer(kind=5), 0, 10, B.ERR_DTYPE),
+        (_layer(kind=-1), 0, 10, B.ERR_DTYPE),
+        (_layer(kind=B.EMBEDDING, X=P + 4, lddy=32), 0, 10, B.ERR_INVALID_ARG),     # ids are int64
+        (_layer(kind=B.EMBEDDING, lddy=31), 0, 10, B.ERR_INVALID_ARG),
+        (_layer(kind=B.EMBEDDING, lddy=32, split_k=2), 0, 10, B.ERR_INVALID_ARG),
+        (_layer(kind=B.RMSNORM, out=2, lddy=32), 0, 10, B.ERR_INVALID_ARG),
+        (_layer(kind=B.RMSNORM, out=1, lddy=32, norm_eps=-1e-6), 0, 10, B.ERR_INVALID_ARG),
+        (_layer(kind=B.LAYERNORM, out=1, lddy=32, norm_eps=float("nan")), 0, 10, B.ERR_INVALID_ARG),
         (_layer(split_k=65), 0, 10, B.ERR_INVALID_ARG),
         (_layer(reserved=1), 0, 10, B.ERR_INVALID_ARG),
         (_layer(kind=B.VECTOR, out=2), 0, 10, B.ERR_INVALID_ARG),
@@ -164,6 +171,12 @@ def test_device_calls_reject_bad_arguments_without_launching():
     assert lib.chunkft_chunk_wgrad(C.byref(sp), 0, 100, P, 0, P, 799, None) == B.ERR_WORKSPACE
     assert lib.chunkft_chunk_wgrad(C.byref(sp), 0, 100, P, 0, P + 4, 800, None) == B.ERR_WORKSPACE
     assert lib.chunkft_wgrad_adamw_fused(C.byref(sp), 0, 100, P, P, P, P, C.byref(hp), None, 0, None) == B.ERR_WORKSPACE
+    # the self-normalising kinds need 8 bytes per token for the statistics
+    nm = _layer(kind=B.RMSNORM, out=1, lddy=32, norm_eps=1e-6)
+    assert lib.chunkft_workspace_bytes(C.byref(nm), 0, 32) == 16 * 8
+    assert lib.chunkft_chunk_wgrad(C.byref(nm), 0, 32, P, 0, None, 0, None) == B.ERR_WORKSPACE
+    assert lib.chunkft_chunk_wgrad(C.byref(nm), 0, 32, P, 0, P, 127, None) == B.ERR_WORKSPACE
+    assert lib.chunkft_wgrad_adamw_fused(C.byref(nm), 0, 32, P, P, P, P, C.byref(hp), None, 0, None) == B.ERR_WORKSPACE
     # AdamW hyper-parameters and sizes
     for bad in (B.hparams(1e-4, 0.9, 0.999, 1e-8, 0.01, 0), B.hparams(1e-4, 1.0, 0.999, 1e-8, 0.01, 1),
                 B.hparams(1e-4, 0.9, -0.1, 1e-8, 0.01, 1), B.hparams(-1.0, 0.9, 0.999, 1e-8, 0.01, 1),
