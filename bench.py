@@ -201,6 +201,8 @@ def main():
 
 
 def sweep(torch, B, dev, hp):
+    import numpy as np
+
     """Plain and fused call on device-generated Gaussian operands of other shapes (same recipe:
     X ~ N(0,1), dY ~ N(0,1e-3), two-scale token rows for the lm_head shape), median of 10."""
     gen = torch.Generator(device=dev)
@@ -247,6 +249,28 @@ def sweep(torch, B, dev, hp):
     scale = torch.where(torch.rand(4096, 1, device=dev, generator=gen) < 0.1, 1e-2, 1e-4)
     for mib in (4, 16, 64, 256, 512):
         one("lm_head 128256x4096", 128256, 4096, 4096, mib << 19, scale)
+
+    # embedding table of the same shape (HBM-bound row gather): ids with heavy-tailed frequencies
+    vocab, dim, T = 128256, 4096, 4096
+    ranks = (torch.exp(torch.rand(T, device=dev, generator=gen) * float(np.log(vocab + 1.0))) - 1.0).long().clamp_(max=vocab - 1)
+    ids = torch.randperm(vocab, device=dev, generator=gen)[ranks].contiguous()
+    dY = (torch.randn(T, dim, device=dev, generator=gen) * 1e-3).to(torch.bfloat16)
+    W = (torch.randn(vocab * dim, device=dev, generator=gen) * 0.02).to(torch.bfloat16)
+    for mib in (64, 512):
+        E = mib << 19
+        begin = (vocab * dim - E) // 2 + 37
+        end = begin + E
+        layer = B.make_layer(B.EMBEDDING, ids, dY, vocab, dim)
+        g = torch.empty(E, dtype=torch.float32, device=dev)
+        master = W[begin:end].float()
+        m, v = torch.zeros_like(master), torch.zeros_like(master)
+        h = B.hparams(step=1, **hp)
+        t_w = timed(lambda: B.chunkft_chunk_wgrad(layer, begin, end, g))
+        t_f = timed(lambda: B.chunkft_wgrad_adamw_fused(layer, begin, end, W, master, m, v, h))
+        rows.append({"shape": "embedding 128256x4096", "T": T, "chunk_MiB": mib, "bound": "hbm",
+                     "wgrad_ms": round(t_w, 4), "wgrad_gbps": round(4.0 * E / t_w / 1e6, 1),
+                     "fused_ms": round(t_f, 4), "fused_gbps": round(26.0 * E / t_f / 1e6, 1),
+                     "fused_frac_of_hbm_peak": round(26.0 * E / t_f / 1e6 / PEAK_HBM_GBPS, 4)})
     return rows
 
 

@@ -137,8 +137,9 @@ typedef struct {
   const void* X;     /* (device) LINEAR: [T, in] layer input.  VECTOR: [T, in] the
                         normalised activations that the scale multiplies.
                         RMSNORM / LAYERNORM: [T, in] the operator's raw input.
-                        EMBEDDING: T token ids as int64 (ids outside the table
-                        rows of the range are ignored) */
+                        EMBEDDING: T <= 16384 token ids as int64 (ids outside the
+                        table rows of the range are ignored; a longer batch is
+                        passed in pieces with accumulate = 1) */
   int64_t ldx;       /* row stride of X in elements, >= in (EMBEDDING: ignored) */
   const void* dY;    /* (device) LINEAR: [T, out] output gradient.  Others: [T, in] */
   int64_t lddy;      /* row stride of dY in elements */

@@ -38,6 +38,7 @@ Checked check_layer(const chunkft_layer* L, int64_t begin, int64_t end) {
   if (one_d && L->out != 1) return c;
   if (L->kind != CHUNKFT_LINEAR && L->split_k > 1) return c;
   if (norm && !(L->norm_eps >= 0.0 && std::isfinite(L->norm_eps))) return c;
+  if (embed && L->T > kMaxEmbeddingTokens) return c;
   if (!embed && L->ldx < L->in) return c;
   if (L->lddy < (L->kind == CHUNKFT_LINEAR ? L->out : L->in)) return c;
   if (L->in > kMaxI64 / L->out) { c.status = CHUNKFT_ERR_OVERFLOW; return c; }

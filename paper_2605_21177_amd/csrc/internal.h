@@ -67,7 +67,9 @@ int launch_colsum(const WgradProblem& p, int dtype, int mode, const Sinks& s, vo
 // stats is a device scratch of 2 * T floats.
 int launch_norm_wgrad(const WgradProblem& p, int dtype, bool subtract_mean, float eps, float* stats, int mode,
                       const Sinks& s, void* stream);
-// Embedding table: p.X holds the int64 token ids, p.dY is [T, in], the table is [out, in].
+// Embedding table: p.X holds the int64 token ids, p.dY is [T, in], the table is [out, in];
+// at most kMaxEmbeddingTokens tokens per call.
+constexpr int64_t kMaxEmbeddingTokens = 16384;
 int launch_embed_wgrad(const WgradProblem& p, int dtype, int mode, const Sinks& s, void* stream);
 // g = sum over slabs (EMIT_STORE / EMIT_ACCUM) or AdamW on that sum (EMIT_ADAMW).
 // W_at_begin is already offset to the first element.

@@ -949,14 +949,21 @@ __global__ __launch_bounds__(256) void norm_stats_kernel(const T* X, int64_t ldx
 // ---------------------------------------------------------------------------
 // embedding table gradient: g[r, :] = sum over the tokens t with ids[t] = r of dY[t, :]
 // ---------------------------------------------------------------------------
-// One wave per table row of the chunk, kEmbRows rows per workgroup.  A wave walks the token
-// ids 64 at a time, keeps those that name its row (ballot) and adds their dY rows in
-// ascending token order: no atomics, the order of the sum is fixed.  A lane holds the
-// columns 256 i + 4 lane + e (i < kEmbIter, e < 4) of the block of 256 kEmbIter columns the
-// workgroup covers (blockIdx.y), so loads and stores of a wave are 1 KB (fp32) pieces.
-// HBM-bound: the rows are written (or updated) once, whether any token names them or not.
-constexpr int kEmbRows = 4;
-constexpr int kEmbIter = 8;
+// A workgroup of 8 waves owns kEmbRows = 64 consecutive table rows and a block of 1024
+// columns (blockIdx.y).  It first turns the token ids into "which of my rows, if any" in LDS
+// (one coalesced pass over the ids per workgroup), its first wave compacts that in place into
+// the short list of tokens that hit any of the 64 rows (token order kept), and then every
+// wave takes 8 of the rows one after the other: it walks the list, picks the entries of its
+// row and adds their dY rows in ascending token order -- no atomics, the order of the sum is
+// fixed.  The loads of four tokens are issued before their additions, so a row that many
+// tokens name (token frequencies are heavy-tailed) does not cost one memory latency per
+// token.  A lane holds the columns 256 i + 4 lane + e (i < kEmbIter, e < 4), so loads and
+// stores of a wave are 1 KB (fp32) pieces.  HBM-bound: the rows are written (or updated)
+// once, whether any token names them or not.
+constexpr int kEmbWaves = 8;
+constexpr int kEmbRows = 64;       // rows per workgroup, kEmbRows / kEmbWaves per wave
+constexpr int kEmbIter = 4;        // 256-column pieces per workgroup
+constexpr int kEmbTok = 16384;     // most tokens per call (their list lives in LDS)
 
 template <typename T> __device__ __forceinline__ void load4_as_f32(const T* p, int valid, float (&o)[4]);
 template <> __device__ __forceinline__ void load4_as_f32<float>(const float* p, int valid, float (&o)[4]) {
@@ -981,59 +988,107 @@ template <> __device__ __forceinline__ void load4_as_f32<unsigned short>(const u
 }
 
 template <typename T, int MODE>
-__global__ __launch_bounds__(64 * kEmbRows) void embed_wgrad_kernel(const WgradProblem p, const Sinks s) {
+__global__ __launch_bounds__(64 * kEmbWaves) void embed_wgrad_kernel(const WgradProblem p, const Sinks s) {
+  __shared__ int list[kEmbTok];
+  __shared__ int list_len;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t row = p.begin / p.in + (int64_t)blockIdx.x * kEmbRows + wave;
-  if (row > (p.end - 1) / p.in) return;           // no barrier below: a wave may leave alone
+  const int64_t row_base = p.begin / p.in + (int64_t)blockIdx.x * kEmbRows;
+  const int64_t row_last = (p.end - 1) / p.in;
   const int64_t cbase = (int64_t)blockIdx.y * (256 * kEmbIter);
   const int64_t* ids = (const int64_t*)p.X;
   const T* dY = (const T*)p.dY;
-  float acc[kEmbIter][4];
+  const int n = (int)p.T;                                   // <= kEmbTok, checked by the launcher
+  for (int i = threadIdx.x; i < n; i += 64 * kEmbWaves) {
+    const int64_t d = ids[i] - row_base;
+    list[i] = (d >= 0 && d < kEmbRows) ? (int)d : -1;
+  }
+  __syncthreads();
+  // wave 0: in-place compaction to entries (token << 6 | row), in token order; the write
+  // position never passes the read position
+  if (wave == 0) {
+    int count = 0;
+    for (int t0 = 0; t0 < n; t0 += 64) {
+      const int w = t0 + lane < n ? list[t0 + lane] : -1;
+      const unsigned long long hits = __ballot(w >= 0);
+      if (w >= 0) list[count + __popcll(hits & ((1ull << lane) - 1ull))] = ((t0 + lane) << 6) | w;
+      count += __popcll(hits);
+    }
+    if (lane == 0) list_len = count;
+  }
+  __syncthreads();
+  const int len = list_len;
+  const int64_t E = p.end - p.begin;
+
+  for (int sub = 0; sub < kEmbRows / kEmbWaves; ++sub) {
+    const int local = sub * kEmbWaves + wave;               // consecutive rows go to different waves
+    const int64_t row = row_base + local;
+    if (row > row_last) break;
+    float acc[kEmbIter][4];
 #pragma unroll
-  for (int i = 0; i < kEmbIter; ++i)
+    for (int i = 0; i < kEmbIter; ++i)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) acc[i][e] = 0.f;
-  for (int64_t t0 = 0; t0 < p.T; t0 += 64) {
-    const int64_t t = t0 + lane;
-    unsigned long long hits = __ballot(t < p.T && ids[t] == row);
-    while (hits) {
-      const int b = __ffsll((long long)hits) - 1;
-      hits &= hits - 1;
-      const T* src = dY + (t0 + b) * p.lddy;
+      for (int e = 0; e < 4; ++e) acc[i][e] = 0.f;
+    // NT tokens at a time: all their loads, then their additions in token order
+    auto add_rows = [&](auto ntc, int ta, int tb, int tc, int td) {
+      constexpr int NT = decltype(ntc)::value;
+      const int tok[4] = {ta, tb, tc, td};
+      float x[NT][kEmbIter][4];
 #pragma unroll
-      for (int i = 0; i < kEmbIter; ++i) {
-        const int64_t c = cbase + i * 256 + 4 * lane;
-        if (c < p.in) {
-          float x[4];
-          load4_as_f32<T>(src + c, (int)(p.in - c < 4 ? p.in - c : 4), x);
+      for (int k = 0; k < NT; ++k) {
+        const T* src = dY + (int64_t)tok[k] * p.lddy;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) acc[i][e] += x[e];
+        for (int i = 0; i < kEmbIter; ++i) {
+          const int64_t c = cbase + i * 256 + 4 * lane;
+          if (c < p.in) load4_as_f32<T>(src + c, (int)(p.in - c < 4 ? p.in - c : 4), x[k][i]);
+          else x[k][i][0] = x[k][i][1] = x[k][i][2] = x[k][i][3] = 0.f;
         }
       }
+#pragma unroll
+      for (int k = 0; k < NT; ++k)
+#pragma unroll
+        for (int i = 0; i < kEmbIter; ++i)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[i][e] += x[k][i][e];
+    };
+    int q0 = 0, q1 = 0, q2 = 0, pending = 0;               // the last tokens found, oldest in q2
+    for (int j = 0; j < len; ++j) {
+      const int e = list[j];                                // the same for every lane
+      if ((e & 63) != local) continue;
+      const int t = e >> 6;
+      if (pending == 3) {
+        add_rows(IntC<4>{}, q2, q1, q0, t);
+        pending = 0;
+      } else {
+        q2 = q1; q1 = q0; q0 = t;
+        ++pending;
+      }
     }
-  }
-  const int64_t E = p.end - p.begin;
+    if (pending == 3) { add_rows(IntC<2>{}, q2, q1, 0, 0); add_rows(IntC<1>{}, q0, 0, 0, 0); }
+    else if (pending == 2) add_rows(IntC<2>{}, q1, q0, 0, 0);
+    else if (pending == 1) add_rows(IntC<1>{}, q0, 0, 0, 0);
+
 #pragma unroll
-  for (int i = 0; i < kEmbIter; ++i) {
-    const int64_t c = cbase + i * 256 + 4 * lane;
-    if (c >= p.in) continue;
-    const int64_t flat = row * p.in + c;
-    if (flat >= p.begin && flat + 4 <= p.end && c + 4 <= p.in) {
-      const int64_t k = flat - p.begin;
-      Vec4Sink d;
-      d.g = s.g + k;
-      d.master = s.master + k;
-      d.m = s.m + k;
-      d.v = s.v + k;
-      d.W = s.w_kind == W_BF16 ? (void*)((unsigned short*)s.W + flat) : (void*)((float*)s.W + flat);
-      const State4 st = load_state4<MODE>(d);
-      const f32x4_u val = {acc[i][0], acc[i][1], acc[i][2], acc[i][3]};
-      finish4<MODE>(d, s.w_kind, s.c, val, st);
-    } else {
+    for (int i = 0; i < kEmbIter; ++i) {
+      const int64_t c = cbase + i * 256 + 4 * lane;
+      if (c >= p.in) continue;
+      const int64_t flat = row * p.in + c;
+      if (flat >= p.begin && flat + 4 <= p.end && c + 4 <= p.in) {
+        const int64_t k = flat - p.begin;
+        Vec4Sink d;
+        d.g = s.g + k;
+        d.master = s.master + k;
+        d.m = s.m + k;
+        d.v = s.v + k;
+        d.W = s.w_kind == W_BF16 ? (void*)((unsigned short*)s.W + flat) : (void*)((float*)s.W + flat);
+        const State4 st = load_state4<MODE>(d);
+        const f32x4_u val = {acc[i][0], acc[i][1], acc[i][2], acc[i][3]};
+        finish4<MODE>(d, s.w_kind, s.c, val, st);
+      } else {
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (c + e < p.in && flat + e >= p.begin && flat + e < p.end)
-          emit<MODE>(s, E, 0, flat + e - p.begin, flat + e, acc[i][e]);
+        for (int e = 0; e < 4; ++e)
+          if (c + e < p.in && flat + e >= p.begin && flat + e < p.end)
+            emit<MODE>(s, E, 0, flat + e - p.begin, flat + e, acc[i][e]);
+      }
     }
   }
 }
@@ -1353,9 +1408,9 @@ int launch_norm_wgrad(const WgradProblem& p, int dtype, bool subtract_mean, floa
 template <typename T>
 static int launch_embed_t(const WgradProblem& p, dim3 grid, int mode, const Sinks& s, hipStream_t st) {
   switch (mode) {
-    case EMIT_STORE: hipLaunchKernelGGL((embed_wgrad_kernel<T, EMIT_STORE>), grid, dim3(64 * kEmbRows), 0, st, p, s); break;
-    case EMIT_ACCUM: hipLaunchKernelGGL((embed_wgrad_kernel<T, EMIT_ACCUM>), grid, dim3(64 * kEmbRows), 0, st, p, s); break;
-    default: hipLaunchKernelGGL((embed_wgrad_kernel<T, EMIT_ADAMW>), grid, dim3(64 * kEmbRows), 0, st, p, s); break;
+    case EMIT_STORE: hipLaunchKernelGGL((embed_wgrad_kernel<T, EMIT_STORE>), grid, dim3(64 * kEmbWaves), 0, st, p, s); break;
+    case EMIT_ACCUM: hipLaunchKernelGGL((embed_wgrad_kernel<T, EMIT_ACCUM>), grid, dim3(64 * kEmbWaves), 0, st, p, s); break;
+    default: hipLaunchKernelGGL((embed_wgrad_kernel<T, EMIT_ADAMW>), grid, dim3(64 * kEmbWaves), 0, st, p, s); break;
   }
   return (int)hipGetLastError();
 }
@@ -1363,7 +1418,7 @@ static int launch_embed_t(const WgradProblem& p, dim3 grid, int mode, const Sink
 int launch_embed_wgrad(const WgradProblem& p, int dtype, int mode, const Sinks& s, void* stream) {
   const int64_t rows = (p.end - 1) / p.in - p.begin / p.in + 1;
   const int64_t gx = ceil_div(rows, kEmbRows), gy = ceil_div(p.in, 256 * kEmbIter);
-  if (gx > 0x7fffffff || gy > 65535) return (int)hipErrorInvalidValue;
+  if (gx > 0x7fffffff || gy > 65535 || p.T > kEmbTok) return (int)hipErrorInvalidValue;
   const dim3 grid((unsigned)gx, (unsigned)gy);
   return dtype == 0 ? launch_embed_t<float>(p, grid, mode, s, (hipStream_t)stream)
                     : launch_embed_t<unsigned short>(p, grid, mode, s, (hipStream_t)stream);
