@@ -126,6 +126,28 @@ int chunkft_plan_cycle(const chunkft_tensor_desc* tensors, int32_t n_tensors,
                        chunkft_segment* segs, int64_t segs_cap, int64_t* n_segs);
 
 /* ------------------------------------------------------------------------
+ * Rotating schedule (host only)
+ *
+ * Paper: Algorithm 1, the loop over training steps: the same chunk is optimised
+ * for `interval` consecutive steps, then the next one in round-robin order;
+ * its state is brought in before the first of those steps and sent back after
+ * the last; every chunk counts its own updates for the bias correction.
+ * ---------------------------------------------------------------------- */
+typedef struct {
+  int32_t active;         /* chunk that is optimised at this training step */
+  int32_t load_before;    /* 1: the chunk becomes active at this step */
+  int32_t offload_after;  /* 1: the chunk is switched out after this step */
+  int32_t reserved;       /* written as 0 */
+  int64_t local_step;     /* the chunk's own update count n after this step's
+                             increment: pass it as chunkft_adamw_hparams.step */
+} chunkft_schedule_entry;
+
+/* step >= 0 (training steps count from 0), n_chunks >= 1, interval >= 1.
+ * A pure function of its arguments; writes *out.
+ * Errors: INVALID_ARG, OVERFLOW. */
+int chunkft_schedule_at(int64_t step, int32_t n_chunks, int64_t interval, chunkft_schedule_entry* out);
+
+/* ------------------------------------------------------------------------
  * Layer operands of one backward step
  * ---------------------------------------------------------------------- */
 typedef struct {

@@ -46,6 +46,9 @@ What each function follows:
                            this build's reading: nearest-even).
 * cycle_step            -- Section 3.2: chunks are a disjoint partition, so one
                            cycle applies the chunk update to every element once.
+* rotating_schedule     -- Algorithm 1, the loop over training steps: the active
+                           index, the load / offload steps and the per-chunk
+                           update counters n^(k), simulated step by step.
 * jitter / imbalance    -- Appendix F definitions.
 
 Pins (tests/test_oracle_pins.py): brute-force loops on tiny layers, closed
@@ -169,6 +172,35 @@ def jitter(step_memory: Sequence[float]) -> float:
     """Appendix F: (max_t M_t - min_t M_t) / mean_t M_t."""
     m = np.asarray(step_memory, dtype=np.float64)
     return float((m.max() - m.min()) / m.mean())
+
+
+# --------------------------------------------------------------------------
+# rotating schedule
+# --------------------------------------------------------------------------
+def rotating_schedule(n_steps: int, n_chunks: int, interval: int):
+    """Algorithm 1's outer loop, run for training steps t = 0 .. n_steps - 1.
+
+    Returns one tuple per step: (active chunk k, load_before, offload_after,
+    n^(k) after its increment).  Written as the algorithm states it: an active
+    index that advances after every `interval` steps, a chunk selected as
+    index mod K when t mod interval = 0, one counter per chunk.
+    """
+    if n_chunks < 1 or interval < 1 or n_steps < 0:
+        raise ValueError("need at least one chunk, a positive interval and a non-negative step count")
+    counters = [0] * n_chunks
+    index = 0
+    k = 0
+    out = []
+    for t in range(n_steps):
+        load = t % interval == 0
+        if load:
+            k = index % n_chunks
+        counters[k] += 1
+        offload = t % interval == interval - 1
+        out.append((k, load, offload, counters[k]))
+        if offload:
+            index += 1
+    return out
 
 
 # --------------------------------------------------------------------------

@@ -63,6 +63,11 @@ class Layer(C.Structure):
                 ("norm_eps", C.c_double)]
 
 
+class ScheduleEntry(C.Structure):
+    _fields_ = [("active", C.c_int32), ("load_before", C.c_int32), ("offload_after", C.c_int32),
+                ("reserved", C.c_int32), ("local_step", C.c_int64)]
+
+
 class ChunkFTError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -104,6 +109,8 @@ def lib() -> C.CDLL:
         L.chunkft_status_string.argtypes = [C.c_int]
         L.chunkft_version.restype = C.c_int
         L.chunkft_version.argtypes = []
+        L.chunkft_schedule_at.restype = C.c_int
+        L.chunkft_schedule_at.argtypes = [C.c_int64, C.c_int32, C.c_int64, C.POINTER(ScheduleEntry)]
         L.chunkft_calib_mfma_bf16.restype = C.c_int
         L.chunkft_calib_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double),
                                               C.c_void_p]
@@ -113,7 +120,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("chunkft_plan_cycle", "chunkft_split_k", "chunkft_workspace_bytes", "chunkft_chunk_wgrad",
            "chunkft_adamw_chunk", "chunkft_wgrad_adamw_fused", "chunkft_status_string",
-           "chunkft_version", "chunkft_calib_mfma_bf16")
+           "chunkft_version", "chunkft_calib_mfma_bf16", "chunkft_schedule_at")
 
 
 def status_string(status: int) -> str:
@@ -244,3 +251,14 @@ def chunkft_calib_mfma_bf16(random_operands: bool, steps: int = 4000, stream=Non
     if st != OK:
         raise ChunkFTError(st, "chunkft_calib_mfma_bf16")
     return tf.value, mhz.value
+
+
+def chunkft_schedule_at(step: int, n_chunks: int, interval: int, check: bool = True):
+    """(active chunk, load_before, offload_after, local_step) of a training step, or the status."""
+    e = ScheduleEntry()
+    st = lib().chunkft_schedule_at(step, n_chunks, interval, C.byref(e))
+    if st != OK:
+        if check:
+            raise ChunkFTError(st, "chunkft_schedule_at")
+        return st
+    return e.active, bool(e.load_before), bool(e.offload_after), e.local_step

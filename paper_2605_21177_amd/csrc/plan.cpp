@@ -135,3 +135,25 @@ extern "C" int chunkft_plan_cycle(const chunkft_tensor_desc* tensors, int32_t n_
   greedy(ts, budget, chunks, segs);
   return CHUNKFT_OK;
 }
+
+// Closed form of the rotating schedule: with H = interval and K chunks, step t lies in
+// visit t / H, which goes to chunk (t / H) mod K and is that chunk's visit number
+// t / (H K) (counting from 0); the chunk has then been updated H times per earlier visit
+// plus (t mod H) + 1 times in this one.
+extern "C" int chunkft_schedule_at(int64_t step, int32_t n_chunks, int64_t interval, chunkft_schedule_entry* out) {
+  if (!out || step < 0 || n_chunks < 1 || interval < 1) return CHUNKFT_ERR_INVALID_ARG;
+  const int64_t visit = step / interval, within = step % interval;
+  if (interval > INT64_MAX / n_chunks) {
+    // a cycle longer than int64: the step lies in the first cycle
+    out->local_step = within + 1;
+  } else {
+    const int64_t earlier_visits = step / (interval * n_chunks);
+    if (earlier_visits > (INT64_MAX - within - 1) / interval) return CHUNKFT_ERR_OVERFLOW;
+    out->local_step = earlier_visits * interval + within + 1;
+  }
+  out->active = (int32_t)(visit % n_chunks);
+  out->load_before = within == 0;
+  out->offload_after = within == interval - 1;
+  out->reserved = 0;
+  return CHUNKFT_OK;
+}

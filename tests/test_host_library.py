@@ -223,3 +223,17 @@ def test_calibration_call_validates_before_touching_the_device():
     for rnd, steps in bad:
         assert lib.chunkft_calib_mfma_bf16(rnd, steps, C.byref(tf), C.byref(mhz), None) == B.ERR_INVALID_ARG
     assert lib.chunkft_calib_mfma_bf16(1, 8, None, C.byref(mhz), None) == B.ERR_INVALID_ARG
+
+
+def test_schedule_matches_the_simulated_algorithm():
+    for K, H in ((1, 1), (1, 4), (2, 1), (3, 2), (5, 3), (7, 10)):
+        ref = O.rotating_schedule(4 * K * H + 3, K, H)
+        for t, want in enumerate(ref):
+            assert B.chunkft_schedule_at(t, K, H) == want
+    # far into training, values stay exact
+    big = 10 ** 15
+    k, load, off, n = B.chunkft_schedule_at(big, 7, 1000)
+    assert k == (big // 1000) % 7 and n == (big // 7000) * 1000 + big % 1000 + 1
+    assert B.chunkft_schedule_at((1 << 62), 3, (1 << 62))[3] == 1
+    for bad in ((-1, 3, 2), (0, 0, 2), (0, 3, 0)):
+        assert B.chunkft_schedule_at(*bad, check=False) == B.ERR_INVALID_ARG

@@ -472,3 +472,39 @@ def test_norm_weight_wgrad_against_library_autograd_and_closed_forms(subtract_me
     np.testing.assert_allclose((a * a).mean(axis=1), 1.0, rtol=1e-12)
     if subtract_mean:
         np.testing.assert_allclose(a.mean(axis=1), 0.0, atol=1e-13)
+
+
+# ---------------------------------------------------------------- rotating schedule
+def test_rotating_schedule_hand_worked_and_invariants():
+    # K = 3 chunks, interval 2: chunks 0 0 1 1 2 2 0 0 ..., counters 1 2 1 2 1 2 3 4 ...
+    got = O.rotating_schedule(8, 3, 2)
+    assert [g[0] for g in got] == [0, 0, 1, 1, 2, 2, 0, 0]
+    assert [g[3] for g in got] == [1, 2, 1, 2, 1, 2, 3, 4]
+    assert [g[1] for g in got] == [True, False] * 4
+    assert [g[2] for g in got] == [False, True] * 4
+    # interval 1: plain round robin, every step loads and offloads
+    got = O.rotating_schedule(7, 4, 1)
+    assert [g[0] for g in got] == [0, 1, 2, 3, 0, 1, 2]
+    assert all(g[1] and g[2] for g in got)
+    assert [g[3] for g in got] == [1, 1, 1, 1, 2, 2, 2]
+    # one chunk: always active, the counter is the step count
+    assert [g[3] for g in O.rotating_schedule(5, 1, 3)] == [1, 2, 3, 4, 5]
+    for K, H in itertools.product((1, 2, 5), (1, 3, 4)):
+        n = 3 * K * H + 2
+        got = O.rotating_schedule(n, K, H)
+        # over whole cycles every chunk is active exactly H steps per cycle
+        cyc = got[:3 * K * H]
+        for k in range(K):
+            assert sum(1 for g in cyc if g[0] == k) == 3 * H
+        # the counters of all chunks add up to the number of steps taken
+        last = {}
+        for g in got:
+            last[g[0]] = g[3]
+        assert sum(last.values()) == n
+        # a chunk's counter rises by exactly one each step it is active
+        seen = {}
+        for g in got:
+            assert g[3] == seen.get(g[0], 0) + 1
+            seen[g[0]] = g[3]
+    with pytest.raises(ValueError):
+        O.rotating_schedule(3, 0, 1)
