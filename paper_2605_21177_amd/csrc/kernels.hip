@@ -1407,10 +1407,14 @@ int launch_norm_wgrad(const WgradProblem& p, int dtype, bool subtract_mean, floa
 
 template <typename T>
 static int launch_embed_t(const WgradProblem& p, dim3 grid, int mode, const Sinks& s, hipStream_t st) {
+  // The update streams seven arrays: it runs 8 % faster with one workgroup per CU than with the
+  // two that fit (4.06 against 3.73 TB/s), so that mode asks for LDS it does not use; the plain
+  // gradient only writes and is faster with two.
+  const size_t pad = mode == EMIT_ADAMW ? 40 * 1024 : 0;
   switch (mode) {
-    case EMIT_STORE: hipLaunchKernelGGL((embed_wgrad_kernel<T, EMIT_STORE>), grid, dim3(64 * kEmbWaves), 0, st, p, s); break;
-    case EMIT_ACCUM: hipLaunchKernelGGL((embed_wgrad_kernel<T, EMIT_ACCUM>), grid, dim3(64 * kEmbWaves), 0, st, p, s); break;
-    default: hipLaunchKernelGGL((embed_wgrad_kernel<T, EMIT_ADAMW>), grid, dim3(64 * kEmbWaves), 0, st, p, s); break;
+    case EMIT_STORE: hipLaunchKernelGGL((embed_wgrad_kernel<T, EMIT_STORE>), grid, dim3(64 * kEmbWaves), pad, st, p, s); break;
+    case EMIT_ACCUM: hipLaunchKernelGGL((embed_wgrad_kernel<T, EMIT_ACCUM>), grid, dim3(64 * kEmbWaves), pad, st, p, s); break;
+    default: hipLaunchKernelGGL((embed_wgrad_kernel<T, EMIT_ADAMW>), grid, dim3(64 * kEmbWaves), pad, st, p, s); break;
   }
   return (int)hipGetLastError();
 }
