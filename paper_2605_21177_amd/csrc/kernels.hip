@@ -6,11 +6,17 @@
 //                       AdamW straight from the accumulators.
 //   wgrad_simt_kernel   the same contraction with fp32 FMAs for the fp32 configuration
 //                       and for shapes the MFMA kernel's 16-byte loads cannot take.
-//   colsum_kernel       1-D scale-vector gradient sum_t dY[t,j] * X[t,j].
+//   wgrad_edge_kernel   the up-to-9 partial / unaligned rows of a chunk that has too few
+//                       rows for the MFMA kernel to carry them (plain FMA).
+//   colsum_kernel       1-D scale-vector gradient sum_t dY[t,j] * X[t,j], X normalised by the
+//                       caller or here (norm_stats_kernel: per-token mean and 1/std).
+//   embed_wgrad_kernel  embedding table gradient: per table row the sum of the dY rows of
+//                       the tokens that name it, in token order.
 //   elementwise_kernel  AdamW over a chunk and/or the fixed-order sum of slab partials.
 //
 // The operations are those of the paper's Section 3.1 (gradient of the active
-// slices only) and Algorithm 1 lines 19-21 (AdamW with the chunk's own counter).
+// slices only, through the chunk-aware operators of Algorithm 1 line 8) and
+// Algorithm 1 lines 19-21 (AdamW with the chunk's own counter).
 
 #include <hip/hip_runtime.h>
 
@@ -171,8 +177,8 @@ __device__ __forceinline__ void finish4(const Vec4Sink& d, int w_kind, const Ada
 //   edge rows: the partial first row, the up-to-7 complete rows before rb0, and
 //   the partial last row -- at most kMaxEdgeRows of them.  The workgroups of the
 //   first tile row, which stream every X column tile anyway, carry them as one
-//   extra 32-row MFMA block; only when there is no body at all (a chunk of a few
-//   rows) does the small FMA edge kernel compute them.
+//   extra 32-row MFMA block; only when the body has at most 128 rows (a chunk of a
+//   few rows) does the small FMA edge kernel compute them.
 struct MfmaParams {
   WgradProblem p;
   int64_t rb0, rb1;
