@@ -219,8 +219,8 @@ def sweep(torch, B, dev, hp):
             ts.append(a.elapsed_time(b))
         return sorted(ts)[len(ts) // 2]
 
-    def one(name, out_f, in_f, T, E, dy_scale):
-        X = torch.randn(T, in_f, device=dev, generator=gen).to(torch.bfloat16)
+    def one(name, out_f, in_f, T, E, dy_scale, x_scale=1.0):
+        X = (torch.randn(T, in_f, device=dev, generator=gen) * x_scale).to(torch.bfloat16)
         dY = (torch.randn(T, out_f, device=dev, generator=gen) * dy_scale).to(torch.bfloat16)
         W = (torch.randn(out_f * in_f, device=dev, generator=gen) * 0.02).to(torch.bfloat16)
         begin = (out_f * in_f - E) // 2 + 37
@@ -263,6 +263,10 @@ def sweep(torch, B, dev, hp):
 
     for T in (1024, 4096, 8192):
         one("up_proj 14336x4096", 14336, 4096, T, 32 << 20, 1e-3)
+    # the same launch on all-zero operands: same instructions, same cycles, but few bits toggle
+    # in the matrix cores, so the part holds a higher clock -- the size of the data-dependent
+    # clock effect on this kernel (not a performance figure)
+    one("up_proj 14336x4096, all-zero operands (clock probe)", 14336, 4096, 1024, 32 << 20, 0.0, x_scale=0.0)
     scale = torch.where(torch.rand(4096, 1, device=dev, generator=gen) < 0.1, 1e-2, 1e-4)
     for mib in (4, 16, 64, 256, 512):
         one("lm_head 128256x4096", 128256, 4096, 4096, mib << 19, scale)
