@@ -109,6 +109,18 @@ def lib() -> C.CDLL:
         L.chunkft_status_string.argtypes = [C.c_int]
         L.chunkft_version.restype = C.c_int
         L.chunkft_version.argtypes = []
+        L.chunkft_mover_create.restype = C.c_int
+        L.chunkft_mover_create.argtypes = [C.POINTER(C.c_void_p)]
+        L.chunkft_mover_destroy.restype = None
+        L.chunkft_mover_destroy.argtypes = [C.c_void_p]
+        L.chunkft_mover_load.restype = C.c_int
+        L.chunkft_mover_load.argtypes = [C.c_void_p] + [C.c_void_p] * 6 + [C.c_int64, C.c_void_p]
+        L.chunkft_mover_await_load.restype = C.c_int
+        L.chunkft_mover_await_load.argtypes = [C.c_void_p, C.c_void_p]
+        L.chunkft_mover_offload.restype = C.c_int
+        L.chunkft_mover_offload.argtypes = [C.c_void_p] + [C.c_void_p] * 6 + [C.c_int64, C.c_void_p]
+        L.chunkft_mover_sync.restype = C.c_int
+        L.chunkft_mover_sync.argtypes = [C.c_void_p]
         L.chunkft_schedule_at.restype = C.c_int
         L.chunkft_schedule_at.argtypes = [C.c_int64, C.c_int32, C.c_int64, C.POINTER(ScheduleEntry)]
         L.chunkft_calib_mfma_bf16.restype = C.c_int
@@ -120,7 +132,9 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("chunkft_plan_cycle", "chunkft_split_k", "chunkft_workspace_bytes", "chunkft_chunk_wgrad",
            "chunkft_adamw_chunk", "chunkft_wgrad_adamw_fused", "chunkft_status_string",
-           "chunkft_version", "chunkft_calib_mfma_bf16", "chunkft_schedule_at")
+           "chunkft_version", "chunkft_calib_mfma_bf16", "chunkft_schedule_at",
+           "chunkft_mover_create", "chunkft_mover_destroy", "chunkft_mover_load", "chunkft_mover_await_load",
+           "chunkft_mover_offload", "chunkft_mover_sync")
 
 
 def status_string(status: int) -> str:
@@ -262,3 +276,43 @@ def chunkft_schedule_at(step: int, n_chunks: int, interval: int, check: bool = T
             raise ChunkFTError(st, "chunkft_schedule_at")
         return st
     return e.active, bool(e.load_before), bool(e.offload_after), e.local_step
+
+
+class Mover:
+    """chunkft_mover_*: asynchronous host <-> device copies of a chunk's (master, m, v)."""
+
+    def __init__(self):
+        h = C.c_void_p()
+        st = lib().chunkft_mover_create(C.byref(h))
+        if st != OK:
+            raise ChunkFTError(st, "chunkft_mover_create")
+        self._h = h
+
+    def close(self):
+        if self._h:
+            lib().chunkft_mover_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st, where):
+        if st != OK:
+            raise ChunkFTError(st, where)
+
+    def load(self, dev3, host3, n, after_stream=None):
+        self._check(lib().chunkft_mover_load(self._h, *[_ptr(t) for t in dev3], *[_ptr(t) for t in host3], n,
+                                             _stream_ptr(after_stream)), "chunkft_mover_load")
+
+    def await_load(self, compute_stream=None):
+        self._check(lib().chunkft_mover_await_load(self._h, _stream_ptr(compute_stream)), "chunkft_mover_await_load")
+
+    def offload(self, host3, dev3, n, compute_stream=None):
+        self._check(lib().chunkft_mover_offload(self._h, *[_ptr(t) for t in host3], *[_ptr(t) for t in dev3], n,
+                                                _stream_ptr(compute_stream)), "chunkft_mover_offload")
+
+    def sync(self):
+        self._check(lib().chunkft_mover_sync(self._h), "chunkft_mover_sync")

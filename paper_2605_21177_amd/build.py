@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libchunkft.so")
 
-SOURCES = ["kernels.hip", "calib.hip", "api.cpp", "plan.cpp"]
+SOURCES = ["kernels.hip", "calib.hip", "api.cpp", "plan.cpp", "mover.cpp"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -423,3 +423,82 @@ def test_calls_replay_from_a_captured_graph():
                                b.view(torch.int32) if b.dtype == torch.float32 else b.view(torch.int16))
         # and the fused state equals the un-fused pair's, replay after replay
         assert torch.equal(st_a[0], st_b[0]) and torch.equal(st_a[1], st_b[1]) and torch.equal(st_a[2], st_b[2])
+
+
+def test_streamed_state_gives_the_resident_trajectory():
+    """Algorithm 1 with the chunk state kept in (pinned) host memory: the next chunk's state is
+    prefetched into the second device buffer set while the active chunk computes, the previous
+    one is offloaded behind it.  After several visits per chunk the host copies must hold,
+    bit for bit, what a run with everything resident on the device produces."""
+    layers = WL.config3(scale=16, T=64)
+    tensors = [(c.out, c.n_in, c.dtype, c.kind) for c in layers]
+    budget = sum(c.numel for c in layers) * 2 // 3 + 2
+    st, chunks, segs = B.chunkft_plan_cycle(tensors, budget)
+    K, interval = len(chunks), 2
+    n_steps = 3 * K * interval
+    dls = [H.DeviceLayer(c) for c in layers]
+    cap = max(ch[2] for ch in chunks)
+
+    def init_state(k):
+        s0, s1, numel, _ = chunks[k]
+        master = torch.empty(numel, dtype=torch.float32)
+        for (t, b, e, off) in segs[s0:s1]:
+            master[off:off + (e - b)] = layers[t].W0.reshape(-1)[b:e].float()
+        return master, torch.zeros(numel), torch.zeros(numel)
+
+    def run_steps(step_fn):
+        Wd = [c.W0.reshape(-1).clone().to(H.DEV) for c in layers]
+        for t in range(n_steps):
+            k, load, off, n = B.chunkft_schedule_at(t, K, interval)
+            master, m, v = step_fn(t, k, load)
+            s0, s1, numel, _ = chunks[k]
+            for (ti, b, e, o) in segs[s0:s1]:
+                layer = dls[ti].layer()
+                cnt = e - b
+                B.chunkft_wgrad_adamw_fused(layer, b, e, Wd[ti], master[o:o + cnt], m[o:o + cnt], v[o:o + cnt],
+                                            B.hparams(step=n, **HP), ws=H.workspace_for(layer, b, e))
+            yield t, k, off
+        torch.cuda.synchronize()
+        yield Wd
+
+    # --- resident run
+    resident = [tuple(x.to(H.DEV) for x in init_state(k)) for k in range(K)]
+    *_, W_res = run_steps(lambda t, k, load: resident[k])
+
+    # --- streamed run: host state pinned, two device sets, prefetch of the next chunk
+    host = [tuple(x.pin_memory() for x in init_state(k)) for k in range(K)]
+    sets = [tuple(torch.empty(cap, dtype=torch.float32, device=H.DEV) for _ in range(3)) for _ in range(2)]
+    mover = B.Mover()
+    visit = {"n": -1}
+
+    def numel_of(k):
+        return chunks[k][2]
+
+    def step_fn(t, k, load):
+        if load:
+            visit["n"] += 1
+            cur = sets[visit["n"] % 2]
+            if visit["n"] == 0:                       # nothing was prefetched for the very first visit
+                mover.load(cur, host[k], numel_of(k))
+            mover.await_load()
+            nxt_k = (k + 1) % K                       # prefetch the next chunk into the other set; its
+            mover.load(sets[(visit["n"] + 1) % 2], host[nxt_k], numel_of(nxt_k))   # old occupant's offload is ahead on the copy stream
+        return sets[visit["n"] % 2]
+
+    gen = run_steps(step_fn)
+    for item in gen:
+        if isinstance(item, list):
+            W_str = item
+            break
+        t, k, off = item
+        if off:
+            # BEFORE the prefetch of the chunk after next can overwrite this set, its offload is enqueued:
+            # the prefetch into this set is only issued at the next visit's first step, after this line
+            mover.offload(host[k], sets[visit["n"] % 2], numel_of(k))
+    mover.sync()
+    mover.close()
+    for k in range(K):
+        for a, b in zip(host[k], resident[k]):
+            assert torch.equal(a, b.cpu()), f"state of chunk {k} differs between streamed and resident run"
+    for a, b in zip(W_str, W_res):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))

@@ -237,3 +237,13 @@ def test_schedule_matches_the_simulated_algorithm():
     assert B.chunkft_schedule_at((1 << 62), 3, (1 << 62))[3] == 1
     for bad in ((-1, 3, 2), (0, 0, 2), (0, 3, 0)):
         assert B.chunkft_schedule_at(*bad, check=False) == B.ERR_INVALID_ARG
+
+
+def test_mover_null_handling_without_a_device():
+    lib = B.lib()
+    lib.chunkft_mover_destroy(None)                                   # allowed
+    assert lib.chunkft_mover_create(None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_mover_sync(None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_mover_await_load(None, None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_mover_load(None, P, P, P, P, P, P, 4, None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_mover_offload(None, P, P, P, P, P, P, 4, None) == B.ERR_INVALID_ARG
