@@ -46,6 +46,10 @@ def main():
                     help="also time the plain and the fused call at longer token counts (the same layer shape, "
                          "T = 4096 and 8192) and on the lm_head shape of configs[4] per chunk size; "
                          "reported under \"sweep\"")
+    ap.add_argument("--stream-state", action="store_true",
+                    help="also time the rotating schedule with the chunk state kept in pinned host memory "
+                         "(three 32Mi-element chunks, interval 4, prefetch of the next chunk and offload of "
+                         "the previous one beside the kernels); reported under \"streamed_state\"")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region, run a plain device copy of known size (256 MiB read, "
                          "256 MiB written, three times): the calibration point for rocprofv3 --pmc "
@@ -186,6 +190,9 @@ def main():
     if args.sweep:
         out["sweep"] = sweep(torch, B, dev, dict(WL.HPARAMS))
 
+    if args.stream_state:
+        out["streamed_state"] = streamed_state(torch, B, dev, layer, begin, end, Wb, h_for=lambda n: B.hparams(step=n, **hp), ws=ws)
+
     if args.copy_probe:
         src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -198,6 +205,55 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(case, begin, end, hp)
     print(json.dumps(out), flush=True)
+
+
+def streamed_state(torch, B, dev, layer, begin, end, W, h_for, ws):
+    """Algorithm 1's streaming on this workload: K = 3 chunks of E elements whose master/m/v live in
+    pinned host memory, interval 4, two device buffer sets.  Every visit runs 4 fused updates on the
+    same layer range (the kernels' cost is what matters here, not which rows they touch) while the
+    next chunk's 12 E bytes come in and the previous chunk's go out.  Reports the wall time per
+    visit against the time of the copies alone and of the kernels alone."""
+    E, K, interval, cycles = end - begin, 3, 4, 2
+    host = [tuple(torch.zeros(E, dtype=torch.float32).pin_memory() for _ in range(3)) for _ in range(K)]
+    sets = [tuple(torch.zeros(E, dtype=torch.float32, device=dev) for _ in range(3)) for _ in range(2)]
+    mover = B.Mover()
+    n_steps = cycles * K * interval
+
+    def run(stream_copies, kernels):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        visit = -1
+        for t in range(n_steps):
+            k, load, off, n = B.chunkft_schedule_at(t, K, interval)
+            if load:
+                visit += 1
+                if stream_copies:
+                    if visit == 0:
+                        mover.load(sets[0], host[k], E)
+                    mover.await_load()
+                    mover.load(sets[(visit + 1) % 2], host[(k + 1) % K], E)
+            cur = sets[visit % 2]
+            if kernels:
+                B.chunkft_wgrad_adamw_fused(layer, begin, end, W, cur[0], cur[1], cur[2], h_for(n), ws=ws)
+            if off and stream_copies:
+                mover.offload(host[k], cur, E)
+        torch.cuda.synchronize()
+        if stream_copies:
+            mover.sync()
+        return (time.perf_counter() - t0) / (cycles * K)
+
+    run(True, True)                                   # warm-up
+    both = run(True, True)
+    copies = run(True, False)
+    kernels = run(False, True)
+    mover.close()
+    per_visit_bytes = 2 * 12.0 * E                    # 12 E in, 12 E out
+    return {"chunks": K, "interval": interval, "chunk_elements": E,
+            "ms_per_visit": round(both * 1e3, 3), "ms_copies_alone": round(copies * 1e3, 3),
+            "ms_kernels_alone": round(kernels * 1e3, 3),
+            "host_link_gbps_each_way": round(12.0 * E / copies / 1e9, 1),
+            "overlap_efficiency": round(max(copies, kernels) / both, 4),
+            "note": "bound by the host link: a visit moves %.0f MB, its kernels take %.2f ms" % (per_visit_bytes / 1e6, kernels * 1e3)}
 
 
 def sweep(torch, B, dev, hp):

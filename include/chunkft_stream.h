@@ -7,7 +7,8 @@
  * of chunkft.h work on.  On a 288 GB device a chunk's state need not leave the GPU at all;
  * this is the mechanism for callers that keep it in host memory as the paper does.
  *
- * A mover owns one copy stream and a few events, no device or host memory.  All copies are
+ * A mover owns two copy streams (one per direction of the host link) and a few events, no
+ * device or host memory.  All copies are
  * ordered by events, never by blocking the host, so the loads of the next chunk and the
  * offload of the previous one run beside the kernels of the active one.  Calls on one mover
  * must come from one thread at a time.
@@ -30,10 +31,10 @@ int chunkft_mover_create(chunkft_mover** out);
 void chunkft_mover_destroy(chunkft_mover* mv);
 
 /* Host -> device.  Copies n floats of each of master, m, v from host arrays (pinned, or the
- * copies are not asynchronous) to device arrays, on the mover's copy stream.  The copies
- * start only after the work enqueued so far on `after_stream` (kernels that may still use
- * the destination arrays) and after every copy enqueued earlier on this mover (an offload
- * out of the same arrays).  Returns at once.
+ * copies are not asynchronous) to device arrays.  The copies start only after the work
+ * enqueued so far on `after_stream` (kernels that may still use the destination arrays) and
+ * after the most recent offload of this mover (which may be out of the same arrays).
+ * Returns at once.
  * Errors: INVALID_ARG (null pointer, n <= 0), HIP. */
 int chunkft_mover_load(chunkft_mover* mv, float* d_master, float* d_m, float* d_v,
                        const float* h_master, const float* h_m, const float* h_v, int64_t n,

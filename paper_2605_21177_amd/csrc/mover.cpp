@@ -1,6 +1,6 @@
 // Asynchronous host <-> device movement of chunk state (declared in chunkft_stream.h):
-// hipMemcpyAsync on a copy stream of its own, ordered against the caller's compute stream
-// by events.  Default stream priority; no host registration (the caller allocates pinned
+// hipMemcpyAsync on two copy streams of its own (one per direction), ordered against the
+// caller's compute stream and against each other by events.  Default stream priority; no host registration (the caller allocates pinned
 // memory itself).
 
 #include <hip/hip_runtime.h>
@@ -10,23 +10,27 @@
 #include "chunkft.h"
 #include "chunkft_stream.h"
 
+// One stream per direction, so that the load of the next chunk and the offload of the previous
+// one use both directions of the host link at once.
 struct chunkft_mover {
-  hipStream_t copy = nullptr;
-  hipEvent_t fence = nullptr;    // "the compute stream got this far"
-  hipEvent_t loaded = nullptr;   // "the most recent load has arrived"
-  bool have_load = false;
+  hipStream_t up = nullptr;        // host -> device
+  hipStream_t down = nullptr;      // device -> host
+  hipEvent_t fence = nullptr;      // "the compute stream got this far"
+  hipEvent_t loaded = nullptr;     // "the most recent load has arrived"
+  hipEvent_t offloaded = nullptr;  // "the most recent offload has left the device arrays"
+  bool have_load = false, have_offload = false;
 };
 
 namespace {
-int copy3(chunkft_mover* mv, float* const dst[3], const float* const src[3], int64_t n, hipMemcpyKind kind) {
+int copy3(hipStream_t on, float* const dst[3], const float* const src[3], int64_t n, hipMemcpyKind kind) {
   const size_t bytes = static_cast<size_t>(n) * sizeof(float);
   for (int i = 0; i < 3; ++i)
-    if (hipMemcpyAsync(dst[i], src[i], bytes, kind, mv->copy) != hipSuccess) return CHUNKFT_ERR_HIP;
+    if (hipMemcpyAsync(dst[i], src[i], bytes, kind, on) != hipSuccess) return CHUNKFT_ERR_HIP;
   return CHUNKFT_OK;
 }
-int order_after(chunkft_mover* mv, void* stream) {
+int order_after(chunkft_mover* mv, hipStream_t copy, void* stream) {
   if (hipEventRecord(mv->fence, static_cast<hipStream_t>(stream)) != hipSuccess) return CHUNKFT_ERR_HIP;
-  if (hipStreamWaitEvent(mv->copy, mv->fence, 0) != hipSuccess) return CHUNKFT_ERR_HIP;
+  if (hipStreamWaitEvent(copy, mv->fence, 0) != hipSuccess) return CHUNKFT_ERR_HIP;
   return CHUNKFT_OK;
 }
 }  // namespace
@@ -36,9 +40,11 @@ extern "C" int chunkft_mover_create(chunkft_mover** out) {
   *out = nullptr;
   chunkft_mover* mv = new (std::nothrow) chunkft_mover();
   if (!mv) return CHUNKFT_ERR_HIP;
-  if (hipStreamCreateWithFlags(&mv->copy, hipStreamNonBlocking) != hipSuccess ||
+  if (hipStreamCreateWithFlags(&mv->up, hipStreamNonBlocking) != hipSuccess ||
+      hipStreamCreateWithFlags(&mv->down, hipStreamNonBlocking) != hipSuccess ||
       hipEventCreateWithFlags(&mv->fence, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&mv->loaded, hipEventDisableTiming) != hipSuccess) {
+      hipEventCreateWithFlags(&mv->loaded, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&mv->offloaded, hipEventDisableTiming) != hipSuccess) {
     chunkft_mover_destroy(mv);
     return CHUNKFT_ERR_HIP;
   }
@@ -48,12 +54,14 @@ extern "C" int chunkft_mover_create(chunkft_mover** out) {
 
 extern "C" void chunkft_mover_destroy(chunkft_mover* mv) {
   if (!mv) return;
-  if (mv->copy) {
-    hipStreamSynchronize(mv->copy);
-    hipStreamDestroy(mv->copy);
-  }
+  for (hipStream_t st : {mv->up, mv->down})
+    if (st) {
+      hipStreamSynchronize(st);
+      hipStreamDestroy(st);
+    }
   if (mv->fence) hipEventDestroy(mv->fence);
   if (mv->loaded) hipEventDestroy(mv->loaded);
+  if (mv->offloaded) hipEventDestroy(mv->offloaded);
   delete mv;
 }
 
@@ -61,13 +69,15 @@ extern "C" int chunkft_mover_load(chunkft_mover* mv, float* d_master, float* d_m
                                   const float* h_master, const float* h_m, const float* h_v, int64_t n,
                                   void* after_stream) {
   if (!mv || !d_master || !d_m || !d_v || !h_master || !h_m || !h_v || n <= 0) return CHUNKFT_ERR_INVALID_ARG;
-  int r = order_after(mv, after_stream);
+  int r = order_after(mv, mv->up, after_stream);
   if (r != CHUNKFT_OK) return r;
+  // the arrays may still be on their way out
+  if (mv->have_offload && hipStreamWaitEvent(mv->up, mv->offloaded, 0) != hipSuccess) return CHUNKFT_ERR_HIP;
   float* const dst[3] = {d_master, d_m, d_v};
   const float* const src[3] = {h_master, h_m, h_v};
-  r = copy3(mv, dst, src, n, hipMemcpyHostToDevice);
+  r = copy3(mv->up, dst, src, n, hipMemcpyHostToDevice);
   if (r != CHUNKFT_OK) return r;
-  if (hipEventRecord(mv->loaded, mv->copy) != hipSuccess) return CHUNKFT_ERR_HIP;
+  if (hipEventRecord(mv->loaded, mv->up) != hipSuccess) return CHUNKFT_ERR_HIP;
   mv->have_load = true;
   return CHUNKFT_OK;
 }
@@ -83,14 +93,19 @@ extern "C" int chunkft_mover_offload(chunkft_mover* mv, float* h_master, float* 
                                      const float* d_master, const float* d_m, const float* d_v, int64_t n,
                                      void* compute_stream) {
   if (!mv || !d_master || !d_m || !d_v || !h_master || !h_m || !h_v || n <= 0) return CHUNKFT_ERR_INVALID_ARG;
-  const int r = order_after(mv, compute_stream);
+  int r = order_after(mv, mv->down, compute_stream);
   if (r != CHUNKFT_OK) return r;
   float* const dst[3] = {h_master, h_m, h_v};
   const float* const src[3] = {d_master, d_m, d_v};
-  return copy3(mv, dst, src, n, hipMemcpyDeviceToHost);
+  r = copy3(mv->down, dst, src, n, hipMemcpyDeviceToHost);
+  if (r != CHUNKFT_OK) return r;
+  if (hipEventRecord(mv->offloaded, mv->down) != hipSuccess) return CHUNKFT_ERR_HIP;
+  mv->have_offload = true;
+  return CHUNKFT_OK;
 }
 
 extern "C" int chunkft_mover_sync(chunkft_mover* mv) {
   if (!mv) return CHUNKFT_ERR_INVALID_ARG;
-  return hipStreamSynchronize(mv->copy) == hipSuccess ? CHUNKFT_OK : CHUNKFT_ERR_HIP;
+  if (hipStreamSynchronize(mv->up) != hipSuccess) return CHUNKFT_ERR_HIP;
+  return hipStreamSynchronize(mv->down) == hipSuccess ? CHUNKFT_OK : CHUNKFT_ERR_HIP;
 }
