@@ -50,6 +50,10 @@ def main():
                     help="also time the rotating schedule with the chunk state kept in pinned host memory "
                          "(three 32Mi-element chunks, interval 4, prefetch of the next chunk and offload of "
                          "the previous one beside the kernels); reported under \"streamed_state\"")
+    ap.add_argument("--plan-sweep", action="store_true",
+                    help="also run the cycle planner over the whole Llama-3-8B tensor list for several chunk "
+                         "counts and report the byte imbalance and the memory jitter it implies, beside a "
+                         "layer-wise partition (host only); reported under \"plan_sweep\"")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region, run a plain device copy of known size (256 MiB read, "
                          "256 MiB written, three times): the calibration point for rocprofv3 --pmc "
@@ -193,6 +197,9 @@ def main():
     if args.stream_state:
         out["streamed_state"] = streamed_state(torch, B, dev, layer, begin, end, Wb, h_for=lambda n: B.hparams(step=n, **hp), ws=ws)
 
+    if args.plan_sweep:
+        out["plan_sweep"] = plan_sweep(B)
+
     if args.copy_probe:
         src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -205,6 +212,45 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(case, begin, end, hp)
     print(json.dumps(out), flush=True)
+
+
+def plan_sweep(B):
+    """The planner on every tensor of a Llama-3-8B-shaped model in model order, with the training
+    cost per element (bf16 parameter + fp32 gradient, master, m, v = 18 B).  For each target chunk
+    count: chunks produced, the largest deviation of a chunk's cost from the mean (the imbalance
+    bound of the jitter analysis) and the jitter (max - min) / mean of the step memory 2 M + B(C_k),
+    activations left out; the same for a partition by layer, which is what layer-wise rotating
+    methods use."""
+    h, kv, ff, vocab, n_layers = 4096, 1024, 14336, 128256, 32
+    tensors = [(vocab, h, B.BF16, B.EMBEDDING)]
+    for _ in range(n_layers):
+        tensors += [(1, h, B.BF16, B.RMSNORM), (h, h, B.BF16, B.LINEAR), (kv, h, B.BF16, B.LINEAR),
+                    (kv, h, B.BF16, B.LINEAR), (h, h, B.BF16, B.LINEAR), (1, h, B.BF16, B.RMSNORM),
+                    (ff, h, B.BF16, B.LINEAR), (ff, h, B.BF16, B.LINEAR), (h, ff, B.BF16, B.LINEAR)]
+    tensors += [(1, h, B.BF16, B.RMSNORM), (vocab, h, B.BF16, B.LINEAR)]
+    numel = [r * c for r, c, _, _ in tensors]
+    M = sum(numel)
+    total_cost = 18 * M
+
+    def stats(costs):
+        mean = sum(costs) / len(costs)
+        mem = [2 * M + c for c in costs]
+        return {"chunks": len(costs), "max_cost_GiB": round(max(costs) / 2 ** 30, 3),
+                "imbalance_MiB": round(max(abs(c - mean) for c in costs) / 2 ** 20, 6),
+                "jitter": round((max(mem) - min(mem)) / (sum(mem) / len(mem)), 7)}
+
+    rows = []
+    budgets = [("%d chunks" % K, -(-total_cost // K) + (-(-(-total_cost // K))) % 18) for K in (7, 32, 100)]
+    budgets += [("%d GiB" % gib, gib << 30) for gib in (1, 2, 4, 8)]
+    for label, budget in budgets:
+        for name, flags in (("greedy", B.PLAN_TRAINING_COST), ("balanced", B.PLAN_TRAINING_COST | B.PLAN_BALANCED)):
+            _, chunks, _ = B.chunkft_plan_cycle(tensors, budget, flags)
+            rows.append({"budget": label, "planner": name, **stats([c[3] for c in chunks])})
+    # layer-wise partition: embedding | each decoder layer | final norm + head
+    layer_numel = [numel[0]] + [sum(numel[1 + 9 * i:10 + 9 * i]) for i in range(n_layers)] + [numel[-2] + numel[-1]]
+    rows.append({"budget": "-", "planner": "one partition per layer (for contrast)",
+                 **stats([18 * x for x in layer_numel])})
+    return {"model": "Llama-3-8B shapes, %d tensors, %.3f G parameters" % (len(tensors), M / 1e9), "rows": rows}
 
 
 def streamed_state(torch, B, dev, layer, begin, end, W, h_for, ws):
