@@ -51,6 +51,19 @@ Pass greedy(const std::vector<Costed>& ts, int64_t budget, chunkft_chunk* chunks
     int64_t pos = 0;
     const int64_t n = ts[t].numel, s = ts[t].cost;
     while (pos < n) {
+      // Counting only, at the start of a chunk: the chunks that this tensor fills completely
+      // all look alike, so they are counted in one step (a 2^60-element tensor under a small
+      // budget would otherwise take 2^50 trips).
+      if (!chunks && !segs && filled == 0 && room == budget) {
+        const int64_t per_chunk = budget / s;
+        const int64_t whole = per_chunk > 0 ? (n - pos) / per_chunk : 0;
+        if (whole > 1) {
+          p.n_chunks += whole - 1;
+          p.n_segs += whole - 1;
+          pos += (whole - 1) * per_chunk;
+          seg_first = p.n_segs;
+        }
+      }
       int64_t take = room / s;
       if (take > n - pos) take = n - pos;
       if (take == 0) {       // not one more element of this tensor fits
