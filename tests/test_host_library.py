@@ -247,3 +247,19 @@ def test_mover_null_handling_without_a_device():
     assert lib.chunkft_mover_await_load(None, None) == B.ERR_INVALID_ARG
     assert lib.chunkft_mover_load(None, P, P, P, P, P, P, 4, None) == B.ERR_INVALID_ARG
     assert lib.chunkft_mover_offload(None, P, P, P, P, P, P, 4, None) == B.ERR_INVALID_ARG
+
+
+def test_plan_counts_astronomic_chunk_numbers_at_once():
+    """A size query for a 2^60-element tensor under a 100-byte budget returns the count
+    (the closed form for one dtype) instead of walking 2^55 chunks."""
+    import ctypes as C
+    lib = B.lib()
+    t = (B.TensorDesc * 2)(B.TensorDesc(1 << 40, 1 << 20, B.BF16, B.LINEAR), B.TensorDesc(3, 7, B.BF16, B.LINEAR))
+    nc, ns = C.c_int64(-1), C.c_int64(-1)
+    st = lib.chunkft_plan_cycle(t, 2, 100, 0, None, 0, C.byref(nc), None, 0, C.byref(ns))
+    assert st == B.ERR_BUFFER_TOO_SMALL
+    total = (1 << 60) + 21
+    assert nc.value == -(-total // 50)
+    # the first tensor ends a chunk exactly (2^60 is not a multiple of 50: 2^60 % 50 = 26 elements in
+    # its last chunk, which the 21 elements of the second tensor join)
+    assert ns.value == -(-(1 << 60) // 50) + 1
