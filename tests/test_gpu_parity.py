@@ -148,6 +148,33 @@ def test_bf16_forced_token_split(split_k):
     assert B.chunkft_split_k(layer, begin, end) == split_k
 
 
+def test_bf16_random_shapes_and_ranges():
+    """Seeded random layers (sizes that are multiples of 8, so the MFMA path takes them), token
+    counts with ragged last slabs, ranges from one element to the whole tensor, with and without
+    a forced token split: every branch of the tile kernel (partial tiles in both directions, edge
+    rows folded or not, body-less chunks) against the oracle."""
+    rng = np.random.default_rng(20250521)
+    for case_no in range(28):
+        out = 8 * int(rng.integers(1, 90))
+        n_in = 8 * int(rng.integers(1, 75))
+        T = int(rng.integers(1, 330))
+        case = WL.linear_case(rng, f"rand{case_no}", out, n_in, T, WL.BF16, 1e-3)
+        numel = out * n_in
+        kind = case_no % 4
+        if kind == 0:
+            begin, end = 0, numel
+        elif kind == 1:
+            begin = int(rng.integers(0, numel))
+            end = begin + 1 + int(rng.integers(0, min(numel - begin, 3 * n_in)))
+        else:
+            begin = int(rng.integers(0, numel - 1))
+            end = int(rng.integers(begin + 1, numel + 1))
+        split = None if case_no % 3 else int(rng.integers(2, 5))
+        print(f"[random-case] {case_no}: {out}x{n_in} T={T} [{begin},{end}) split={split}", flush=True)
+        _full_check(case, begin, end, split_k=split, check_accum=(case_no % 5 == 0), warm=(case_no % 2 == 1),
+                    step=1 + case_no % 3)
+
+
 def test_bf16_unaligned_shape_takes_fma_path():
     rng = np.random.default_rng(78)
     case = WL.linear_case(rng, "odd", 137, 100, 53, WL.BF16, 1e-3)   # in, out not multiples of 8
