@@ -155,7 +155,7 @@ typedef struct {
   int32_t dtype;     /* chunkft_dtype of X, dY (and of W in the fused call) */
   int64_t out, in;   /* W shape; the 1-D kinds: out = 1, in = vector length;
                         EMBEDDING: out = table rows, in = embedding width */
-  int64_t T;         /* tokens */
+  int64_t T;         /* tokens, 1 .. 2^30 */
   const void* X;     /* (device) LINEAR: [T, in] layer input.  VECTOR: [T, in] the
                         normalised activations that the scale multiplies.
                         RMSNORM / LAYERNORM: [T, in] the operator's raw input.

@@ -33,6 +33,7 @@ Checked check_layer(const chunkft_layer* L, int64_t begin, int64_t end) {
   if (L->dtype != CHUNKFT_F32 && L->dtype != CHUNKFT_BF16) { c.status = CHUNKFT_ERR_DTYPE; return c; }
   if (!L->X || !L->dY) return c;
   if (L->out <= 0 || L->in <= 0 || L->T <= 0) return c;
+  if (L->T > (int64_t(1) << 30)) return c;          // the kernels count the tokens of a slab in 32 bits
   if (L->reserved != 0) return c;
   if (L->split_k < 0 || L->split_k > 64) return c;
   if (one_d && L->out != 1) return c;

@@ -133,6 +133,7 @@ def test_device_calls_reject_bad_arguments_without_launching():
     cases = [
         (_layer(X=None), 0, 10, B.ERR_INVALID_ARG),
         (_layer(T=0), 0, 10, B.ERR_INVALID_ARG),
+        (_layer(T=(1 << 30) + 1), 0, 10, B.ERR_INVALID_ARG),
         (_layer(ldx=31), 0, 10, B.ERR_INVALID_ARG),
         (_layer(lddy=63), 0, 10, B.ERR_INVALID_ARG),
         (_layer(dtype=7), 0, 10, B.ERR_DTYPE),
