@@ -89,8 +89,8 @@ extern "C" int chunkft_calib_mfma_bf16(int32_t random_operands, int32_t steps, d
     *shader_mhz = (double)h[0] / (double)h[1] * 100.0;
     rc = CHUNKFT_OK;
   } while (false);
-  if (e0) hipEventDestroy(e0);
-  if (e1) hipEventDestroy(e1);
-  hipFree(buf);
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipFree(buf);
   return rc;
 }

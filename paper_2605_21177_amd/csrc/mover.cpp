@@ -56,12 +56,12 @@ extern "C" void chunkft_mover_destroy(chunkft_mover* mv) {
   if (!mv) return;
   for (hipStream_t st : {mv->up, mv->down})
     if (st) {
-      hipStreamSynchronize(st);
-      hipStreamDestroy(st);
+      (void)hipStreamSynchronize(st);      // clean-up: nothing to report to
+      (void)hipStreamDestroy(st);
     }
-  if (mv->fence) hipEventDestroy(mv->fence);
-  if (mv->loaded) hipEventDestroy(mv->loaded);
-  if (mv->offloaded) hipEventDestroy(mv->offloaded);
+  if (mv->fence) (void)hipEventDestroy(mv->fence);
+  if (mv->loaded) (void)hipEventDestroy(mv->loaded);
+  if (mv->offloaded) (void)hipEventDestroy(mv->offloaded);
   delete mv;
 }
 
