@@ -998,9 +998,12 @@ __global__ __launch_bounds__(64 * kEmbWaves) void embed_wgrad_kernel(const Wgrad
   __shared__ int list[kEmbTok];
   __shared__ int list_len;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t row_base = p.begin / p.in + (int64_t)blockIdx.x * kEmbRows;
+  // column blocks of one group of rows are neighbours in the launch order, so that a row's
+  // pieces are touched at about the same time
+  const int n_cblk = (int)((p.in + 256 * kEmbIter - 1) / (256 * kEmbIter));
+  const int64_t row_base = p.begin / p.in + (int64_t)(blockIdx.x / n_cblk) * kEmbRows;
   const int64_t row_last = (p.end - 1) / p.in;
-  const int64_t cbase = (int64_t)blockIdx.y * (256 * kEmbIter);
+  const int64_t cbase = (int64_t)(blockIdx.x % n_cblk) * (256 * kEmbIter);
   const int64_t* ids = (const int64_t*)p.X;
   const T* dY = (const T*)p.dY;
   const int n = (int)p.T;                                   // <= kEmbTok, checked by the launcher
@@ -1034,6 +1037,23 @@ __global__ __launch_bounds__(64 * kEmbWaves) void embed_wgrad_kernel(const Wgrad
     for (int i = 0; i < kEmbIter; ++i)
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc[i][e] = 0.f;
+    // The row's state is requested first, so that it travels while the hit list is walked.
+    Vec4Sink d[kEmbIter];
+    State4 st[kEmbIter];
+    bool whole[kEmbIter];
+#pragma unroll
+    for (int i = 0; i < kEmbIter; ++i) {
+      const int64_t c = cbase + i * 256 + 4 * lane;
+      const int64_t flat = row * p.in + c;
+      whole[i] = c + 4 <= p.in && flat >= p.begin && flat + 4 <= p.end;
+      const int64_t k = flat - p.begin;
+      d[i].g = s.g + k;
+      d[i].master = s.master + k;
+      d[i].m = s.m + k;
+      d[i].v = s.v + k;
+      d[i].W = s.w_kind == W_BF16 ? (void*)((unsigned short*)s.W + flat) : (void*)((float*)s.W + flat);
+      if (whole[i]) st[i] = load_state4<MODE>(d[i]);
+    }
     // NT tokens at a time: all their loads, then their additions in token order
     auto add_rows = [&](auto ntc, int ta, int tb, int tc, int td) {
       constexpr int NT = decltype(ntc)::value;
@@ -1078,17 +1098,9 @@ __global__ __launch_bounds__(64 * kEmbWaves) void embed_wgrad_kernel(const Wgrad
       const int64_t c = cbase + i * 256 + 4 * lane;
       if (c >= p.in) continue;
       const int64_t flat = row * p.in + c;
-      if (flat >= p.begin && flat + 4 <= p.end && c + 4 <= p.in) {
-        const int64_t k = flat - p.begin;
-        Vec4Sink d;
-        d.g = s.g + k;
-        d.master = s.master + k;
-        d.m = s.m + k;
-        d.v = s.v + k;
-        d.W = s.w_kind == W_BF16 ? (void*)((unsigned short*)s.W + flat) : (void*)((float*)s.W + flat);
-        const State4 st = load_state4<MODE>(d);
+      if (whole[i]) {
         const f32x4_u val = {acc[i][0], acc[i][1], acc[i][2], acc[i][3]};
-        finish4<MODE>(d, s.w_kind, s.c, val, st);
+        finish4<MODE>(d[i], s.w_kind, s.c, val, st[i]);
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
@@ -1428,8 +1440,8 @@ static int launch_embed_t(const WgradProblem& p, dim3 grid, int mode, const Sink
 int launch_embed_wgrad(const WgradProblem& p, int dtype, int mode, const Sinks& s, void* stream) {
   const int64_t rows = (p.end - 1) / p.in - p.begin / p.in + 1;
   const int64_t gx = ceil_div(rows, kEmbRows), gy = ceil_div(p.in, 256 * kEmbIter);
-  if (gx > 0x7fffffff || gy > 65535 || p.T > kEmbTok) return (int)hipErrorInvalidValue;
-  const dim3 grid((unsigned)gx, (unsigned)gy);
+  if (gy > 65535 || gx > 0x7fffffff / gy || p.T > kEmbTok) return (int)hipErrorInvalidValue;
+  const dim3 grid((unsigned)(gx * gy));
   return dtype == 0 ? launch_embed_t<float>(p, grid, mode, s, (hipStream_t)stream)
                     : launch_embed_t<unsigned short>(p, grid, mode, s, (hipStream_t)stream);
 }
