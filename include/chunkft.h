@@ -159,7 +159,7 @@ typedef struct {
   const void* X;     /* (device) LINEAR: [T, in] layer input.  VECTOR: [T, in] the
                         normalised activations that the scale multiplies.
                         RMSNORM / LAYERNORM: [T, in] the operator's raw input.
-                        EMBEDDING: T <= 16384 token ids as int64 (ids outside the
+                        EMBEDDING: T <= 8192 token ids as int64 (ids outside the
                         table rows of the range are ignored; a longer batch is
                         passed in pieces with accumulate = 1) */
   int64_t ldx;       /* row stride of X in elements, >= in (EMBEDDING: ignored) */

@@ -69,7 +69,7 @@ int launch_norm_wgrad(const WgradProblem& p, int dtype, bool subtract_mean, floa
                       const Sinks& s, void* stream);
 // Embedding table: p.X holds the int64 token ids, p.dY is [T, in], the table is [out, in];
 // at most kMaxEmbeddingTokens tokens per call.
-constexpr int64_t kMaxEmbeddingTokens = 16384;
+constexpr int64_t kMaxEmbeddingTokens = 8192;
 int launch_embed_wgrad(const WgradProblem& p, int dtype, int mode, const Sinks& s, void* stream);
 // g = sum over slabs (EMIT_STORE / EMIT_ACCUM) or AdamW on that sum (EMIT_ADAMW).
 // W_at_begin is already offset to the first element.

@@ -961,15 +961,19 @@ __global__ __launch_bounds__(256) void norm_stats_kernel(const T* X, int64_t ldx
 // the short list of tokens that hit any of the 64 rows (token order kept), and then every
 // wave takes 8 of the rows one after the other: it walks the list, picks the entries of its
 // row and adds their dY rows in ascending token order -- no atomics, the order of the sum is
-// fixed.  The loads of four tokens are issued before their additions, so a row that many
-// tokens name (token frequencies are heavy-tailed) does not cost one memory latency per
-// token.  A lane holds the columns 256 i + 4 lane + e (i < kEmbIter, e < 4), so loads and
+// fixed.  The loads of four tokens are issued before their additions, so a row that several
+// tokens name does not cost one memory latency per token; a row that very many name (token
+// frequencies are heavy-tailed: the commonest token can be a tenth of a batch) is summed by
+// all eight waves together, wave w taking every eighth hit, and the eight partial sums are
+// added in wave order -- still a fixed order.  A lane holds the columns 256 i + 4 lane + e (i < kEmbIter, e < 4), so loads and
 // stores of a wave are 1 KB (fp32) pieces.  HBM-bound: the rows are written (or updated)
 // once, whether any token names them or not.
 constexpr int kEmbWaves = 8;
 constexpr int kEmbRows = 64;       // rows per workgroup, kEmbRows / kEmbWaves per wave
 constexpr int kEmbIter = 4;        // 256-column pieces per workgroup
-constexpr int kEmbTok = 16384;     // most tokens per call (their list lives in LDS)
+constexpr int kEmbTok = 8192;      // most tokens per call (their list lives in LDS)
+constexpr int kEmbHot = 32;        // hits from which a row is summed by all waves together ...
+constexpr int kEmbHotMax = 2;      // ... for at most this many rows of a workgroup
 
 template <typename T> __device__ __forceinline__ void load4_as_f32(const T* p, int valid, float (&o)[4]);
 template <> __device__ __forceinline__ void load4_as_f32<float>(const float* p, int valid, float (&o)[4]) {
@@ -996,7 +1000,10 @@ template <> __device__ __forceinline__ void load4_as_f32<unsigned short>(const u
 template <typename T, int MODE>
 __global__ __launch_bounds__(64 * kEmbWaves) void embed_wgrad_kernel(const WgradProblem p, const Sinks s) {
   __shared__ int list[kEmbTok];
-  __shared__ int list_len;
+  __shared__ int list_len, n_hot;
+  __shared__ int hits_of[kEmbRows], hot_row[kEmbHotMax];
+  __shared__ float part[kEmbWaves][256 * kEmbIter];
+  __shared__ float hot_sum[kEmbHotMax][256 * kEmbIter];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   // column blocks of one group of rows are neighbours in the launch order, so that a row's
   // pieces are touched at about the same time
@@ -1028,6 +1035,83 @@ __global__ __launch_bounds__(64 * kEmbWaves) void embed_wgrad_kernel(const Wgrad
   const int len = list_len;
   const int64_t E = p.end - p.begin;
 
+  // NT tokens at a time into `into`: all their loads, then their additions in token order
+  auto add_tokens = [&](float (&into)[kEmbIter][4], auto ntc, int ta, int tb, int tc, int td) {
+    constexpr int NT = decltype(ntc)::value;
+    const int tok[4] = {ta, tb, tc, td};
+    float x[NT][kEmbIter][4];
+#pragma unroll
+    for (int k = 0; k < NT; ++k) {
+      const T* src = dY + (int64_t)tok[k] * p.lddy;
+#pragma unroll
+      for (int i = 0; i < kEmbIter; ++i) {
+        const int64_t c = cbase + i * 256 + 4 * lane;
+        if (c < p.in) load4_as_f32<T>(src + c, (int)(p.in - c < 4 ? p.in - c : 4), x[k][i]);
+        else x[k][i][0] = x[k][i][1] = x[k][i][2] = x[k][i][3] = 0.f;
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < NT; ++k)
+#pragma unroll
+      for (int i = 0; i < kEmbIter; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) into[i][e] += x[k][i][e];
+  };
+  // Sum of the hits of local row `r` that `mine(ordinal)` selects, ordinal = 0, 1, ... in token order.
+  auto gather = [&](float (&into)[kEmbIter][4], int r, auto mine) {
+    int q0 = 0, q1 = 0, q2 = 0, pending = 0, ordinal = 0;     // the last tokens found, oldest in q2
+    for (int j = 0; j < len; ++j) {
+      const int e = list[j];                                  // the same for every lane
+      if ((e & 63) != r) continue;
+      if (!mine(ordinal++)) continue;
+      const int t = e >> 6;
+      if (pending == 3) {
+        add_tokens(into, IntC<4>{}, q2, q1, q0, t);
+        pending = 0;
+      } else {
+        q2 = q1; q1 = q0; q0 = t;
+        ++pending;
+      }
+    }
+    if (pending == 3) { add_tokens(into, IntC<2>{}, q2, q1, 0, 0); add_tokens(into, IntC<1>{}, q0, 0, 0, 0); }
+    else if (pending == 2) add_tokens(into, IntC<2>{}, q1, q0, 0, 0);
+    else if (pending == 1) add_tokens(into, IntC<1>{}, q0, 0, 0, 0);
+  };
+
+  // ---- rows with very many hits: all waves together
+  for (int i = threadIdx.x; i < kEmbRows; i += 64 * kEmbWaves) hits_of[i] = 0;
+  __syncthreads();
+  for (int j = threadIdx.x; j < len; j += 64 * kEmbWaves) atomicAdd(&hits_of[list[j] & 63], 1);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int nh = 0;
+    for (int r = 0; r < kEmbRows && nh < kEmbHotMax; ++r)
+      if (hits_of[r] >= kEmbHot) hot_row[nh++] = r;
+    n_hot = nh;
+  }
+  __syncthreads();
+  const int nh = n_hot;
+  for (int h = 0; h < nh; ++h) {
+    float pacc[kEmbIter][4];
+#pragma unroll
+    for (int i = 0; i < kEmbIter; ++i)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pacc[i][e] = 0.f;
+    gather(pacc, hot_row[h], [&](int ordinal) { return (ordinal & (kEmbWaves - 1)) == wave; });
+#pragma unroll
+    for (int i = 0; i < kEmbIter; ++i)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) part[wave][i * 256 + 4 * lane + e] = pacc[i][e];
+    __syncthreads();
+    for (int c = threadIdx.x; c < 256 * kEmbIter; c += 64 * kEmbWaves) {
+      float sum = part[0][c];
+#pragma unroll
+      for (int w = 1; w < kEmbWaves; ++w) sum += part[w][c];
+      hot_sum[h][c] = sum;
+    }
+    __syncthreads();
+  }
+
   for (int sub = 0; sub < kEmbRows / kEmbWaves; ++sub) {
     const int local = sub * kEmbWaves + wave;               // consecutive rows go to different waves
     const int64_t row = row_base + local;
@@ -1054,44 +1138,17 @@ __global__ __launch_bounds__(64 * kEmbWaves) void embed_wgrad_kernel(const Wgrad
       d[i].W = s.w_kind == W_BF16 ? (void*)((unsigned short*)s.W + flat) : (void*)((float*)s.W + flat);
       if (whole[i]) st[i] = load_state4<MODE>(d[i]);
     }
-    // NT tokens at a time: all their loads, then their additions in token order
-    auto add_rows = [&](auto ntc, int ta, int tb, int tc, int td) {
-      constexpr int NT = decltype(ntc)::value;
-      const int tok[4] = {ta, tb, tc, td};
-      float x[NT][kEmbIter][4];
+    int hot = -1;
+    for (int h = 0; h < nh; ++h)
+      if (hot_row[h] == local) hot = h;
+    if (hot >= 0) {
 #pragma unroll
-      for (int k = 0; k < NT; ++k) {
-        const T* src = dY + (int64_t)tok[k] * p.lddy;
+      for (int i = 0; i < kEmbIter; ++i)
 #pragma unroll
-        for (int i = 0; i < kEmbIter; ++i) {
-          const int64_t c = cbase + i * 256 + 4 * lane;
-          if (c < p.in) load4_as_f32<T>(src + c, (int)(p.in - c < 4 ? p.in - c : 4), x[k][i]);
-          else x[k][i][0] = x[k][i][1] = x[k][i][2] = x[k][i][3] = 0.f;
-        }
-      }
-#pragma unroll
-      for (int k = 0; k < NT; ++k)
-#pragma unroll
-        for (int i = 0; i < kEmbIter; ++i)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) acc[i][e] += x[k][i][e];
-    };
-    int q0 = 0, q1 = 0, q2 = 0, pending = 0;               // the last tokens found, oldest in q2
-    for (int j = 0; j < len; ++j) {
-      const int e = list[j];                                // the same for every lane
-      if ((e & 63) != local) continue;
-      const int t = e >> 6;
-      if (pending == 3) {
-        add_rows(IntC<4>{}, q2, q1, q0, t);
-        pending = 0;
-      } else {
-        q2 = q1; q1 = q0; q0 = t;
-        ++pending;
-      }
+        for (int e = 0; e < 4; ++e) acc[i][e] = hot_sum[hot][i * 256 + 4 * lane + e];
+    } else {
+      gather(acc, local, [](int) { return true; });
     }
-    if (pending == 3) { add_rows(IntC<2>{}, q2, q1, 0, 0); add_rows(IntC<1>{}, q0, 0, 0, 0); }
-    else if (pending == 2) add_rows(IntC<2>{}, q1, q0, 0, 0);
-    else if (pending == 1) add_rows(IntC<1>{}, q0, 0, 0, 0);
 
 #pragma unroll
     for (int i = 0; i < kEmbIter; ++i) {

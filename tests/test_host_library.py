@@ -142,7 +142,7 @@ def test_device_calls_reject_bad_arguments_without_launching():
         (_layer(kind=B.EMBEDDING, X=P + 4, lddy=32), 0, 10, B.ERR_INVALID_ARG),     # ids are int64
         (_layer(kind=B.EMBEDDING, lddy=31), 0, 10, B.ERR_INVALID_ARG),
         (_layer(kind=B.EMBEDDING, lddy=32, split_k=2), 0, 10, B.ERR_INVALID_ARG),
-        (_layer(kind=B.EMBEDDING, lddy=32, T=16385), 0, 10, B.ERR_INVALID_ARG),            # too many tokens per call
+        (_layer(kind=B.EMBEDDING, lddy=32, T=8193), 0, 10, B.ERR_INVALID_ARG),            # too many tokens per call
         (_layer(kind=B.RMSNORM, out=2, lddy=32), 0, 10, B.ERR_INVALID_ARG),
         (_layer(kind=B.RMSNORM, out=1, lddy=32, norm_eps=-1e-6), 0, 10, B.ERR_INVALID_ARG),
         (_layer(kind=B.LAYERNORM, out=1, lddy=32, norm_eps=float("nan")), 0, 10, B.ERR_INVALID_ARG),
