@@ -738,7 +738,7 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
     const unsigned so_next = (unsigned)(((kt + 1) % C::NS) * C::STAGE_BYTES);
     constexpr int ST_FETCH = FAST ? KM : -1;
     static_for<8>([&](auto ic) {
-      constexpr int i = decltype(ic)::value, a = i / 2, b = i % 2;
+      constexpr int i = decltype(ic)::value, a = i / 2, b = (a & 1) ? 1 - i % 2 : i % 2;
       __builtin_amdgcn_sched_barrier(0);
       acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h0, 2 * a), frag(h0, 8 + 2 * b), acc[a][b], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
@@ -765,7 +765,7 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
     }
     __builtin_amdgcn_s_barrier();
     static_for<8>([&](auto ic) {
-      constexpr int i = decltype(ic)::value, a = i / 2, b = i % 2;
+      constexpr int i = decltype(ic)::value, a = i / 2, b = (a & 1) ? 1 - i % 2 : i % 2;
       __builtin_amdgcn_sched_barrier(0);
       acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(h1, 2 * a), frag(h1, 8 + 2 * b), acc[a][b], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
