@@ -390,8 +390,10 @@ def sweep(torch, B, dev, hp):
         h = B.hparams(step=1, **hp)
         t_w = timed(lambda: B.chunkft_chunk_wgrad(layer, begin, end, g))
         t_f = timed(lambda: B.chunkft_wgrad_adamw_fused(layer, begin, end, W, master, m, v, h))
+        t_a = timed(lambda: B.chunkft_chunk_wgrad(layer, begin, end, g, accumulate=True))
         rows.append({"shape": "embedding 128256x4096", "T": T, "chunk_MiB": mib, "bound": "hbm",
                      "wgrad_ms": round(t_w, 4), "wgrad_gbps": round(4.0 * E / t_w / 1e6, 1),
+                     "wgrad_accumulate_ms": round(t_a, 4),
                      "fused_ms": round(t_f, 4), "fused_gbps": round(26.0 * E / t_f / 1e6, 1),
                      "fused_frac_of_hbm_peak": round(26.0 * E / t_f / 1e6 / PEAK_HBM_GBPS, 4)})
     return rows

@@ -967,7 +967,8 @@ __global__ __launch_bounds__(256) void norm_stats_kernel(const T* X, int64_t ldx
 // all eight waves together, wave w taking every eighth hit, and the eight partial sums are
 // added in wave order -- still a fixed order.  A lane holds the columns 256 i + 4 lane + e (i < kEmbIter, e < 4), so loads and
 // stores of a wave are 1 KB (fp32) pieces.  HBM-bound: the rows are written (or updated)
-// once, whether any token names them or not.
+// once, whether any token names them or not -- except when the result is added to g
+// (accumulation over micro-batches), where only the named rows are touched.
 constexpr int kEmbWaves = 8;
 constexpr int kEmbRows = 64;       // rows per workgroup, kEmbRows / kEmbWaves per wave
 constexpr int kEmbIter = 4;        // 256-column pieces per workgroup
@@ -1034,6 +1035,8 @@ __global__ __launch_bounds__(64 * kEmbWaves) void embed_wgrad_kernel(const Wgrad
   __syncthreads();
   const int len = list_len;
   const int64_t E = p.end - p.begin;
+  // adding to g: rows that no token names stay as they are, their traffic is saved
+  if (MODE == EMIT_ACCUM && len == 0) return;               // the same for every thread
 
   // NT tokens at a time into `into`: all their loads, then their additions in token order
   auto add_tokens = [&](float (&into)[kEmbIter][4], auto ntc, int ta, int tb, int tc, int td) {
@@ -1116,6 +1119,7 @@ __global__ __launch_bounds__(64 * kEmbWaves) void embed_wgrad_kernel(const Wgrad
     const int local = sub * kEmbWaves + wave;               // consecutive rows go to different waves
     const int64_t row = row_base + local;
     if (row > row_last) break;
+    if (MODE == EMIT_ACCUM && hits_of[local] == 0) continue;
     float acc[kEmbIter][4];
 #pragma unroll
     for (int i = 0; i < kEmbIter; ++i)
