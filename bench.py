@@ -54,6 +54,10 @@ def main():
                     help="also run the cycle planner over the whole Llama-3-8B tensor list for several chunk "
                          "counts and report the byte imbalance and the memory jitter it implies, beside a "
                          "layer-wise partition (host only); reported under \"plan_sweep\"")
+    ap.add_argument("--block-cycle", action="store_true",
+                    help="also run one cycle over a whole Llama-3-8B transformer block (configs[2]: q, k, v, o, "
+                         "gate, up, down and two norm vectors, T = 1024) with the planner's chunks for a 256 MiB "
+                         "budget: one fused call per segment, timed per chunk; reported under \"block_cycle\"")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region, run a plain device copy of known size (256 MiB read, "
                          "256 MiB written, three times): the calibration point for rocprofv3 --pmc "
@@ -200,6 +204,9 @@ def main():
     if args.plan_sweep:
         out["plan_sweep"] = plan_sweep(B)
 
+    if args.block_cycle:
+        out["block_cycle"] = block_cycle(torch, B, dev, dict(WL.HPARAMS))
+
     if args.copy_probe:
         src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -300,6 +307,68 @@ def streamed_state(torch, B, dev, layer, begin, end, W, h_for, ws):
             "host_link_gbps_each_way": round(12.0 * E / copies / 1e9, 1),
             "overlap_efficiency": round(max(copies, kernels) / both, 4),
             "note": "bound by the host link: a visit moves %.0f MB, its kernels take %.2f ms" % (per_visit_bytes / 1e6, kernels * 1e3)}
+
+
+def block_cycle(torch, B, dev, hp):
+    """One cycle over the nine tensors of a Llama-3-8B block: plan with a 256 MiB budget, then per
+    chunk one fused call per segment on one stream (a chunk may cross tensors), median of 10."""
+    T = 1024
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(211773)
+    shapes = [("q", 4096, 4096, "h"), ("k", 1024, 4096, "h"), ("v", 1024, 4096, "h"), ("o", 4096, 4096, "a"),
+              ("gate", 14336, 4096, "n"), ("up", 14336, 4096, "n"), ("down", 4096, 14336, "f"),
+              ("norm1", 1, 4096, "x1"), ("norm2", 1, 4096, "x2")]
+    inputs = {}
+
+    def x_for(key, width):
+        if key not in inputs:
+            inputs[key] = torch.randn(T, width, device=dev, generator=gen).to(torch.bfloat16)
+        return inputs[key]
+
+    layers, Ws, tensors = [], [], []
+    for name, out_f, in_f, xkey in shapes:
+        X = x_for(xkey, in_f)
+        dY = (torch.randn(T, out_f if out_f > 1 else in_f, device=dev, generator=gen) * 1e-3).to(torch.bfloat16)
+        kind = B.LINEAR if out_f > 1 else B.VECTOR
+        layers.append(B.make_layer(kind, X, dY, out_f, in_f))
+        Ws.append((torch.randn(out_f * in_f, device=dev, generator=gen) * 0.02).to(torch.bfloat16))
+        tensors.append((out_f, in_f, B.BF16, kind))
+        inputs[name + "_dY"] = dY                         # keeps the tensor alive
+    _, chunks, segs = B.chunkft_plan_cycle(tensors, 256 << 20)
+    h = B.hparams(step=1, **hp)
+    rows = []
+    for k, (s0, s1, numel, cost) in enumerate(chunks):
+        master = torch.empty(numel, dtype=torch.float32, device=dev)
+        for (t, b, e, off) in segs[s0:s1]:
+            master[off:off + e - b] = Ws[t][b:e].float()
+        m, v = torch.zeros_like(master), torch.zeros_like(master)
+        work = []
+        for (t, b, e, off) in segs[s0:s1]:
+            nws = B.chunkft_workspace_bytes(layers[t], b, e)
+            ws = torch.empty(nws, dtype=torch.uint8, device=dev) if nws else None
+            work.append((t, b, e, off, ws))
+
+        def run_chunk():
+            for (t, b, e, off, ws) in work:
+                n = e - b
+                B.chunkft_wgrad_adamw_fused(layers[t], b, e, Ws[t], master[off:off + n], m[off:off + n],
+                                            v[off:off + n], h, ws=ws)
+
+        for _ in range(2):
+            run_chunk()
+        ts = []
+        for _ in range(10):
+            a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); run_chunk(); z.record(); z.synchronize()
+            ts.append(a.elapsed_time(z))
+        ms = sorted(ts)[len(ts) // 2]
+        rows.append({"chunk": k, "segments": [{"tensor": shapes[t][0], "elements": e - b,
+                                               "split_k": B.chunkft_split_k(layers[t], b, e)}
+                                              for (t, b, e, off, ws) in work],
+                     "elements": numel, "ms": round(ms, 4), "ns_per_kilo_element": round(ms * 1e6 / (numel / 1e3), 3),
+                     "tflops": round(2.0 * T * numel / ms / 1e9, 1), "state_gbps": round(26.0 * numel / ms / 1e6, 1)})
+    return {"T": T, "budget_MiB": 256, "tensors": [s[0] for s in shapes], "chunks": rows,
+            "cycle_ms": round(sum(r["ms"] for r in rows), 4)}
 
 
 def sweep(torch, B, dev, hp):
