@@ -1389,11 +1389,12 @@ int launch_mfma_cfg(const WgradProblem& p, int mode, const Sinks& s, hipStream_t
   q.rb1 = rs.rb1;
   q.lead_base = folded ? rs.lead_base : -1;
   q.trail_row = folded ? rs.trail_row : -1;
-  q.tiles_m = (int32_t)ceil_div(rs.rb1 - rs.rb0, C::BM);
-  q.tiles_n = (int32_t)ceil_div(p.in, C::BN);
-  const int64_t n_items = (int64_t)q.tiles_m * q.tiles_n * p.S;
-  if (n_items > 0x3fffffff) return (int)hipErrorInvalidValue;
-  q.n_tile_items = (int32_t)n_items;
+  const int64_t tiles_m = ceil_div(rs.rb1 - rs.rb0, C::BM), tiles_n = ceil_div(p.in, C::BN);
+  if (tiles_m > 0x3fffffff || tiles_n > 0x3fffffff || tiles_m * tiles_n > 0x3fffffff / p.S)
+    return (int)hipErrorInvalidValue;                  // work items are counted in 32 bits
+  q.tiles_m = (int32_t)tiles_m;
+  q.tiles_n = (int32_t)tiles_n;
+  q.n_tile_items = (int32_t)(tiles_m * tiles_n * p.S);
   // Order of the tiles inside an XCD's run of work items.  Plain gradient: groups of 8 tile rows,
   // column tile by column tile (X tiles stay in that L2).  Fused call: row-major, so that the
   // workgroups running side by side in one XCD update adjacent column tiles and the 128-byte
@@ -1438,10 +1439,12 @@ int launch_wgrad_simt(const WgradProblem& p, int dtype, int mode, const Sinks& s
   q.s = s;
   q.r0 = p.begin / p.in;
   const int64_t rows = (p.end - 1) / p.in - q.r0 + 1;
-  q.tiles_m = (int32_t)ceil_div(rows, 64);
-  q.tiles_n = (int32_t)ceil_div(p.in, 64);
-  const int64_t grid = (int64_t)q.tiles_m * q.tiles_n * p.S;
-  if (grid > 0x7fffffff) return (int)hipErrorInvalidValue;
+  const int64_t tiles_m = ceil_div(rows, 64), tiles_n = ceil_div(p.in, 64);
+  if (tiles_m > 0x7fffffff || tiles_n > 0x7fffffff || tiles_m * tiles_n > 0x7fffffff / p.S)
+    return (int)hipErrorInvalidValue;                  // the grid is counted in 32 bits
+  q.tiles_m = (int32_t)tiles_m;
+  q.tiles_n = (int32_t)tiles_n;
+  const int64_t grid = tiles_m * tiles_n * p.S;
   hipStream_t st = (hipStream_t)stream;
   return dtype == 0 ? launch_simt_t<float>(q, (int)grid, mode, st)
                     : launch_simt_t<unsigned short>(q, (int)grid, mode, st);
