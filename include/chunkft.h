@@ -210,6 +210,11 @@ size_t chunkft_workspace_bytes(const chunkft_layer* L, int64_t begin, int64_t en
  *                   aligned; may be NULL when that is 0.  Contents on entry
  *                   are ignored; on return they are unspecified.
  * Only elements [0, end - begin) of g are written; nothing else is touched.
+ * Layout: any 4-byte aligned g is accepted.  The LINEAR kernels run fastest when
+ * g (and master, m, v in the fused call) has the 128-byte phase of the tensor,
+ * ((uintptr_t)g / 4 - begin) % 32 == 0 for a row length that is a multiple of
+ * 32: the 16-byte groups and the memory lines of a row of the chunk are then
+ * those of the same row of W (measured on the fused call: 7 % faster).
  * Errors: INVALID_ARG, RANGE, DTYPE, WORKSPACE, HIP.
  * ---------------------------------------------------------------------- */
 int chunkft_chunk_wgrad(const chunkft_layer* L, int64_t begin, int64_t end,

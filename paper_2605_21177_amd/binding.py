@@ -206,6 +206,21 @@ def make_layer(kind: int, X, dY, out: int, n_in: int, split_k: int = 0, norm_eps
                  split_k, 0, float(norm_eps))
 
 
+def chunk_array(n: int, begin: int, device="cuda", fill=None):
+    """An fp32 device array of n elements for a chunk segment that starts at tensor element
+    `begin` (g, master, m or v), placed so that element i has the 128-byte phase of tensor
+    element begin + i: the 16-byte groups and the memory lines of the array then coincide with
+    those of the tensor's rows, which is the layout the fused call streams fastest (any 4-byte
+    aligned pointer is accepted).  Allocation only."""
+    import torch
+    full = torch.empty(n + 32, dtype=torch.float32, device=device)
+    lead = (begin - full.data_ptr() // 4) % 32
+    view = full[lead:lead + n]
+    if fill is not None:
+        view.copy_(fill)
+    return view
+
+
 def _stream_ptr(stream) -> int:
     import torch
     s = torch.cuda.current_stream() if stream is None else stream

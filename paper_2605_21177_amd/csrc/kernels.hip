@@ -393,6 +393,27 @@ __device__ __forceinline__ void tile_epilogue(const MfmaParams& q, unsigned char
       for (int v = 0; v < 16; ++v) base[((v >> 2) * 8 + (v & 3)) * C::EPI_PITCH] = acc[h * APH + a2][b][v];
     });
     __syncthreads();
+    // The left-over element of this thread (delta != 0): in the fused call its state is requested
+    // now and used after the row loop, so that this second round of loads costs no extra wait.
+    bool lo_ok = false;
+    int64_t lo_i = 0;
+    float lo_val = 0.f, lo_th = 0.f, lo_m = 0.f, lo_v = 0.f;
+    if (delta != 0) {
+      static_assert(C::NT / 4 >= HALF_ROWS, "one thread per left-over element of a staged half tile");
+      const int rr = tid >> 2, e = tid & 3;
+      const int tile_row = (rr / WR) * (2 * WR) + h * WR + rr % WR;
+      const int lc = e < delta ? e : cols_valid - 4 + e;      // cols_valid is a multiple of 8
+      lo_ok = rr < HALF_ROWS && tile_row < rows_valid;
+      if (lo_ok) {
+        lo_i = origin + (int64_t)tile_row * p.in + lc;
+        lo_val = stage[rr * C::EPI_PITCH + sft + lc];
+        if constexpr (MODE == EMIT_ADAMW) {
+          lo_th = q.s.master[lo_i];
+          lo_m = q.s.m[lo_i];
+          lo_v = q.s.v[lo_i];
+        }
+      }
+    }
     if (vec_lane && c4 + 4 <= cols_valid) {
       // RPT rows per trip: their state loads are issued together, then the updates
       // (four measured best for the fused call: 226 us against 228 / 248 us with two / one)
@@ -419,14 +440,16 @@ __device__ __forceinline__ void tile_epilogue(const MfmaParams& q, unsigned char
         }
       }
     }
-    if (delta != 0) {
-      static_assert(C::NT / 4 >= HALF_ROWS, "one thread per left-over element of a staged half tile");
-      const int rr = tid >> 2, e = tid & 3;
-      const int tile_row = (rr / WR) * (2 * WR) + h * WR + rr % WR;
-      const int lc = e < delta ? e : cols_valid - 4 + e;      // cols_valid is a multiple of 8
-      if (rr < HALF_ROWS && tile_row < rows_valid) {
-        const int64_t i = origin + (int64_t)tile_row * p.in + lc;
-        emit<MODE>(q.s, E, slab, i, i + p.begin, stage[rr * C::EPI_PITCH + sft + lc]);
+    if (lo_ok) {
+      if constexpr (MODE == EMIT_ADAMW) {
+        adamw_update(lo_val, lo_th, lo_m, lo_v, q.s.c);
+        q.s.master[lo_i] = lo_th;
+        q.s.m[lo_i] = lo_m;
+        q.s.v[lo_i] = lo_v;
+        if (q.s.w_kind == W_BF16) ((unsigned short*)q.s.W)[lo_i + p.begin] = f32_to_bf16_rne(lo_th);
+        else if (q.s.w_kind == W_F32) ((float*)q.s.W)[lo_i + p.begin] = lo_th;
+      } else {
+        emit<MODE>(q.s, E, slab, lo_i, lo_i + p.begin, lo_val);
       }
     }
   }
@@ -1179,7 +1202,7 @@ struct ElemParams {
   const float* src;     // g (S = 0) or the slab partials [S][n]
   int32_t S;            // 0: src is g itself
   int64_t n;
-  int64_t head;         // elements before the first 4-element group
+  int64_t head;         // elements before the first 4-element group (at most 31)
   float* g_out;         // EMIT_STORE / EMIT_ACCUM
   float* master;
   float* m;
@@ -1216,11 +1239,11 @@ __device__ __forceinline__ void elem_one(const ElemParams& q, int64_t i) {
 template <int MODE, int U = 1>
 __global__ __launch_bounds__(256) void elementwise_kernel(const ElemParams q) {
   const int64_t nvec = (q.n - q.head) >> 2;
-  if (blockIdx.x == 0 && threadIdx.x < 8) {
-    // the few elements before and after the 4-element groups
+  if (blockIdx.x == 0 && threadIdx.x < 36) {
+    // the few elements before (at most 31) and after (at most 3) the 4-element groups
     const int64_t tail0 = q.head + (nvec << 2);
-    const int64_t i = threadIdx.x < 4 ? (int64_t)threadIdx.x : tail0 + (threadIdx.x - 4);
-    const bool ok = threadIdx.x < 4 ? (i < q.head) : (i < q.n);
+    const int64_t i = threadIdx.x < 32 ? (int64_t)threadIdx.x : tail0 + (threadIdx.x - 32);
+    const bool ok = threadIdx.x < 32 ? (i < q.head) : (i < q.n);
     if (ok) elem_one<MODE>(q, i);
   }
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -1511,10 +1534,12 @@ int launch_embed_wgrad(const WgradProblem& p, int dtype, int mode, const Sinks& 
 }
 
 static int launch_elem(ElemParams& q, int mode, hipStream_t st) {
-  // the first 4-element group starts where the fp32 arrays are 16-byte aligned
-  // (judged by the master weights for the update, by the output gradient otherwise)
+  // the first 4-element group starts where the fp32 arrays are 128-byte aligned (judged by the
+  // master weights for the update, by the output gradient otherwise): the 1 KB a wave requests
+  // per array is then eight whole lines; at a 16-byte phase inside a line it is nine, and the
+  // pass 14 % slower (measured)
   const void* ref = mode == EMIT_ADAMW ? (const void*)q.master : (const void*)q.g_out;
-  int64_t head = ((16 - (reinterpret_cast<uintptr_t>(ref) & 15u)) & 15u) / 4;
+  int64_t head = ((128 - (reinterpret_cast<uintptr_t>(ref) & 127u)) & 127u) / 4;
   if (head > q.n) head = q.n;
   q.head = head;
   const int64_t nvec = (q.n - head) >> 2;

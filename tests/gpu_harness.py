@@ -52,18 +52,44 @@ class DeviceLayer:
                             norm_eps=self.case.eps)
 
 
+# When set to a tensor element index, guarded() places element 0 of the fp32 arrays it makes at
+# the 128-byte phase of that element (the layout include/chunkft.h recommends); otherwise the
+# arrays start GUARD elements into a fresh allocation.
+PHASE_OF = None
+
+
+class phase_aligned:
+    """with phase_aligned(begin): chunk arrays are laid out at the phase of tensor element begin."""
+
+    def __init__(self, begin: int):
+        self.begin = begin
+
+    def __enter__(self):
+        global PHASE_OF
+        self.prev, PHASE_OF = PHASE_OF, self.begin
+
+    def __exit__(self, *exc):
+        global PHASE_OF
+        PHASE_OF = self.prev
+
+
 def guarded(n: int, fill=None, dtype=torch.float32):
     """Device array of n elements inside canary bands; returns (full, view)."""
-    full = torch.full((n + 2 * GUARD,), CANARY, dtype=dtype, device=DEV)
-    view = full[GUARD:GUARD + n]
+    lead = GUARD
+    full = torch.full((n + 2 * GUARD + 32,), CANARY, dtype=dtype, device=DEV)
+    if PHASE_OF is not None and dtype == torch.float32:
+        lead += (PHASE_OF - (full.data_ptr() // 4 + GUARD)) % 32
+    view = full[lead:lead + n]
     if fill is not None:
         view.copy_(fill if torch.is_tensor(fill) else torch.as_tensor(fill, dtype=dtype))
+    full._lead, full._n = lead, n
     return full, view
 
 
 def guards_intact(full: torch.Tensor) -> bool:
     c = torch.tensor(CANARY, dtype=full.dtype).item()
-    return bool((full[:GUARD] == c).all().item() and (full[-GUARD:] == c).all().item())
+    lead, n = full._lead, full._n
+    return bool((full[:lead] == c).all().item() and (full[lead + n:] == c).all().item())
 
 
 def workspace_for(layer: B.Layer, begin: int, end: int):

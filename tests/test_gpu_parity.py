@@ -113,6 +113,27 @@ def test_config1_standalone_adamw_elementwise():
         H.assert_elementwise(v, ref[2], 0.0, f"v step {step}")
 
 
+@pytest.mark.parametrize("phase", [0, 1, 3, 4, 17, 31])
+def test_standalone_adamw_at_every_array_phase(phase):
+    """The element-wise pass peels up to 31 leading elements so that its 16-byte groups start on a
+    128-byte line: arrays at several phases inside a line, lengths that leave 0-3 trailing elements."""
+    rng = np.random.default_rng([41, phase])
+    for n in (1, 5, 30, 33, 1000, 4099 + phase):
+        g32 = rng.standard_normal(n).astype(np.float32) * 1e-3
+        th0 = rng.standard_normal(n).astype(np.float32) * 0.02
+        # warm moments that do not cancel against the gradient, so every element is well-conditioned
+        m0 = (g32 * rng.uniform(0.1, 0.9, n)).astype(np.float32)
+        v0 = (g32 * g32 * rng.uniform(0.1, 0.9, n)).astype(np.float32)
+        ref = O.adamw_step(g32, th0, m0, v0, step=3, **HP)
+        with H.phase_aligned(phase):
+            fg, gdev = H.guarded(n, torch.from_numpy(g32))
+            th, m, v = H.gpu_adamw(gdev, th0, m0, v0, None, HP, 3, w_dtype=B.F32)
+        assert H.guards_intact(fg)
+        H.assert_elementwise(th, ref[0], 0.0, f"theta n={n}")
+        H.assert_elementwise(m, ref[1], 0.0, f"m n={n}")
+        H.assert_elementwise(v, ref[2], 0.0, f"v n={n}")
+
+
 # -------------------------------------------------- adversarial ranges, bf16
 def _small_bf16(out=520, n_in=264, T=100, seed=77, sigma_dy=1e-3):
     rng = np.random.default_rng(seed)
@@ -137,6 +158,15 @@ RANGES_520x264 = [
 @pytest.mark.parametrize("begin,end", RANGES_520x264)
 def test_bf16_ranges(begin, end):
     _full_check(_small_bf16(), begin, end)
+
+
+@pytest.mark.parametrize("begin,end", [(0, 520 * 288), (288 * 2 + 33, 288 * 519 + 1), (288 * 8, 288 * 300 + 100),
+                                       (288 * 5 + 77, 288 * 400), (288 * 259 + 287, 288 * 519)])
+def test_bf16_ranges_with_chunk_arrays_at_the_tensor_phase(begin, end):
+    """g, master, m, v laid out so that element i has the 128-byte phase of tensor element begin + i
+    (the recommended layout: whole 16-byte groups per row, no left-over columns)."""
+    with H.phase_aligned(begin):
+        _full_check(_small_bf16(n_in=288), begin, end)
 
 
 @pytest.mark.parametrize("split_k", [2, 3, 4])
