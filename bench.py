@@ -426,11 +426,12 @@ def sweep(torch, B, dev, hp):
         # the next: rotate over enough distinct sets of g / master / m / v that each call finds
         # its set evicted (about 1 GB between two uses of the same set).
         n_sets = max(1, min(16, int((1 << 30) // (16 * E))))
-        gs = [torch.empty(E, dtype=torch.float32, device=dev) for _ in range(n_sets)]
+        gs = [B.chunk_array(E, begin, dev) for _ in range(n_sets)]
         sets = []
+        zero = torch.zeros((), dtype=torch.float32, device=dev)
         for _ in range(n_sets):
-            master = W[begin:end].float()
-            sets.append((master, torch.zeros_like(master), torch.zeros_like(master)))
+            sets.append((B.chunk_array(E, begin, dev, fill=W[begin:end].float()),
+                         B.chunk_array(E, begin, dev, fill=zero), B.chunk_array(E, begin, dev, fill=zero)))
         h = B.hparams(step=1, **hp)
         turn = [0]
 

@@ -179,7 +179,9 @@ typedef struct {
 int chunkft_split_k(const chunkft_layer* L, int64_t begin, int64_t end);
 
 /* Bytes of device workspace the two wgrad entry points need for this call:
- * LINEAR: 0 when S = 1, else S * (end - begin) * 4 for the per-slab partial sums;
+ * LINEAR: 0 when S = 1, else 4 * (S * P + 32) for the per-slab partial sums,
+ * P = end - begin rounded up to a multiple of 32 (the library places them at the
+ * 128-byte phase of the array their sum goes to);
  * RMSNORM / LAYERNORM: 8 * T for the per-token statistics; other kinds 0.
  * Returns 0 also for invalid arguments (the call itself reports those). */
 size_t chunkft_workspace_bytes(const chunkft_layer* L, int64_t begin, int64_t end);

@@ -64,7 +64,7 @@ Checked check_layer(const chunkft_layer* L, int64_t begin, int64_t end) {
   const Split sp = pick_split(L->kind, L->dtype, L->out, L->in, L->T, begin, end, L->split_k, c.mfma);
   p.S = sp.S;
   p.kslab = sp.kslab;
-  if (p.S > 1 && (end - begin) > kMaxI64 / 4 / p.S) { c.status = CHUNKFT_ERR_OVERFLOW; return c; }
+  if (p.S > 1 && (end - begin) > kMaxI64 / 4 / p.S - 64) { c.status = CHUNKFT_ERR_OVERFLOW; return c; }
   c.status = CHUNKFT_OK;
   return c;
 }
@@ -88,10 +88,21 @@ int check_hparams(const chunkft_adamw_hparams* hp, AdamWConsts* out) {
   return CHUNKFT_OK;
 }
 
+// Elements from one slab's partial sums to the next: the chunk length rounded up to a 128-byte line.
+int64_t slab_pitch(const WgradProblem& p) { return (p.end - p.begin + 31) / 32 * 32; }
+
 size_t workspace_need(const chunkft_layer* L, const WgradProblem& p) {
   if (L->kind == CHUNKFT_RMSNORM || L->kind == CHUNKFT_LAYERNORM) return static_cast<size_t>(p.T) * 8u;
   if (p.S <= 1) return 0;
-  return static_cast<size_t>(p.S) * static_cast<size_t>(p.end - p.begin) * 4u;
+  return (static_cast<size_t>(p.S) * static_cast<size_t>(slab_pitch(p)) + 32u) * 4u;
+}
+
+// Where the slab partials start inside the workspace: at the 128-byte phase of the array the sum
+// goes to (g, or master in the fused call), so that the reduction reads and writes whole lines.
+void place_partials(Sinks& s, const WgradProblem& p, void* ws, const float* dst) {
+  const uintptr_t lead = (reinterpret_cast<uintptr_t>(dst) / 4u - reinterpret_cast<uintptr_t>(ws) / 4u) & 31u;
+  s.ws = static_cast<float*>(ws) + lead;
+  s.ws_pitch = slab_pitch(p);
 }
 
 int check_workspace(const chunkft_layer* L, const WgradProblem& p, void* ws, size_t ws_bytes) {
@@ -137,6 +148,7 @@ extern "C" int chunkft_chunk_wgrad(const chunkft_layer* L, int64_t begin, int64_
   Sinks s{};
   s.g = g;
   s.ws = static_cast<float*>(ws);
+  if (c.p.S > 1) place_partials(s, c.p, ws, g);
   const int final_mode = accumulate ? EMIT_ACCUM : EMIT_STORE;
   if (c.p.S <= 1) return run_wgrad(L, c, final_mode, s, stream);
   const int r = run_wgrad(L, c, EMIT_PARTIAL, s, stream);
@@ -189,6 +201,7 @@ extern "C" int chunkft_wgrad_adamw_fused(const chunkft_layer* L, int64_t begin, 
   s.W = W;
   s.w_kind = !W ? W_NONE : (L->dtype == CHUNKFT_BF16 ? W_BF16 : W_F32);
   s.ws = static_cast<float*>(ws);
+  if (c.p.S > 1) place_partials(s, c.p, ws, master);
   if (c.p.S <= 1) return run_wgrad(L, c, EMIT_ADAMW, s, stream);
   const int r = run_wgrad(L, c, EMIT_PARTIAL, s, stream);
   if (r != CHUNKFT_OK) return r;

@@ -20,7 +20,7 @@ struct AdamWConsts {
 enum EmitMode : int {
   EMIT_STORE = 0,    // g[i] = val
   EMIT_ACCUM = 1,    // g[i] += val
-  EMIT_PARTIAL = 2,  // ws[slab * E + i] = val   (split over tokens)
+  EMIT_PARTIAL = 2,  // ws[slab * ws_pitch + i] = val   (split over tokens)
   EMIT_ADAMW = 3     // AdamW on master/m/v[i], low-precision copy at W[flat]
 };
 
@@ -28,7 +28,8 @@ enum WKind : int { W_NONE = 0, W_BF16 = 1, W_F32 = 2 };
 
 struct Sinks {
   float* g;          // EMIT_STORE / EMIT_ACCUM
-  float* ws;         // EMIT_PARTIAL: [S][E]
+  float* ws;         // EMIT_PARTIAL: slab s at ws + s * ws_pitch (also the statistics scratch of the norm kinds)
+  int64_t ws_pitch;  // elements from one slab's partial sums to the next
   float* master;     // EMIT_ADAMW
   float* m;
   float* v;

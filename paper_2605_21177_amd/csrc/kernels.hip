@@ -92,7 +92,7 @@ __device__ __forceinline__ void emit(const Sinks& s, int64_t E, int32_t slab, in
   } else if constexpr (MODE == EMIT_ACCUM) {
     s.g[i] += val;
   } else if constexpr (MODE == EMIT_PARTIAL) {
-    s.ws[(int64_t)slab * E + i] = val;
+    s.ws[(int64_t)slab * s.ws_pitch + i] = val;
   } else {
     float th = s.master[i], mm = s.m[i], vv = s.v[i];
     adamw_update(val, th, mm, vv, s.c);
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(kEdgeThreads) void wgrad_edge_kernel(const EdgePara
       if constexpr (MODE == EMIT_PARTIAL) {
         // the edge rows take all tokens at once: slab 0 carries the sum, the rest zero
         q.s.ws[i] = sum;
-        for (int32_t sl = 1; sl < p.S; ++sl) q.s.ws[(int64_t)sl * E + i] = 0.f;
+        for (int32_t sl = 1; sl < p.S; ++sl) q.s.ws[(int64_t)sl * q.s.ws_pitch + i] = 0.f;
       } else {
         emit<MODE>(q.s, E, 0, i, flat, sum);
       }
@@ -345,7 +345,7 @@ __device__ __forceinline__ void tile_epilogue(const MfmaParams& q, unsigned char
   constexpr int APH = C::TM / 2;          // 32-row accumulator blocks of a wave per half
   constexpr int WR = 32 * APH;            // rows of one wave row in a staged half
   constexpr int HALF_ROWS = C::WM * WR;   // rows staged per pass
-  float* const g_dst = MODE == EMIT_PARTIAL ? q.s.ws + (int64_t)slab * E : q.s.g;
+  float* const g_dst = MODE == EMIT_PARTIAL ? q.s.ws + (int64_t)slab * q.s.ws_pitch : q.s.g;
   // Groups of four columns start where the fp32 destination is 16-byte aligned:
   // at tile-local column delta (the same for every row, because in % 8 == 0).
   // The delta leading and 4 - delta trailing columns of a row that are left over
@@ -1199,9 +1199,10 @@ __global__ __launch_bounds__(64 * kEmbWaves) void embed_wgrad_kernel(const Wgrad
 // element-wise pass: AdamW and/or the sum of slab partials (HBM-bound)
 // ---------------------------------------------------------------------------
 struct ElemParams {
-  const float* src;     // g (S = 0) or the slab partials [S][n]
+  const float* src;     // g (S = 0) or the slab partials, slab sl at src + sl * pitch
   int32_t S;            // 0: src is g itself
   int64_t n;
+  int64_t pitch;
   int64_t head;         // elements before the first 4-element group (at most 31)
   float* g_out;         // EMIT_STORE / EMIT_ACCUM
   float* master;
@@ -1219,7 +1220,7 @@ __device__ __forceinline__ void elem_one(const ElemParams& q, int64_t i) {
     val = q.src[i];
   } else {
     val = q.src[i];
-    for (int32_t sl = 1; sl < q.S; ++sl) val += q.src[(int64_t)sl * q.n + i];
+    for (int32_t sl = 1; sl < q.S; ++sl) val += q.src[(int64_t)sl * q.pitch + i];
   }
   if constexpr (MODE == EMIT_STORE) {
     q.g_out[i] = val;
@@ -1266,7 +1267,7 @@ __global__ __launch_bounds__(256) void elementwise_kernel(const ElemParams q) {
       if (ok[u]) {
         val[u] = __builtin_nontemporal_load((const f32x4_u*)(q.src + i));
         for (int32_t sl = 1; sl < q.S; ++sl)
-          val[u] += __builtin_nontemporal_load((const f32x4_u*)(q.src + (int64_t)sl * q.n + i));
+          val[u] += __builtin_nontemporal_load((const f32x4_u*)(q.src + (int64_t)sl * q.pitch + i));
         st[u] = load_state4<MODE>(d[u]);
       }
     }
@@ -1286,9 +1287,10 @@ constexpr int kNumCU = 256;
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Start delay (units of 8128 cycles) of the second workgroup of each compute unit in the fused
-// call, whose epilogue is long and HBM-bound: measured best at 7-10 for 1024 to 8192 tokens; the
-// plain gradient gains nothing.
-constexpr int kStaggerAdamW = 8;
+// call, whose epilogue is long and HBM-bound: measured best at 6 for 1024 tokens (196 us against
+// 200 us at 8, 208 us at 0), flat between 6 and 10 for 4096 and 8192; the plain gradient gains
+// nothing.
+constexpr int kStaggerAdamW = 6;
 using MainCfg = RingCfg<2, 4>;    // 256 x 256 tiles, four slabs of 33 KB in LDS, one workgroup per compute unit
 using FusedCfg = RingCfg<1, 3>;   // 128 x 256 tiles, three slabs of 25 KB, two workgroups per compute unit
 
@@ -1564,6 +1566,7 @@ int launch_reduce(const float* ws, int32_t S, int64_t E, int mode, const Sinks& 
   q.src = ws;
   q.S = S;
   q.n = E;
+  q.pitch = s.ws_pitch;
   q.g_out = s.g;
   q.master = s.master;
   q.m = s.m;

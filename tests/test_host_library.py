@@ -168,10 +168,10 @@ def test_device_calls_reject_bad_arguments_without_launching():
     # forced split without (enough) workspace
     sp = _layer(T=64, split_k=2)
     assert lib.chunkft_split_k(C.byref(sp), 0, 100) == 2
-    assert lib.chunkft_workspace_bytes(C.byref(sp), 0, 100) == 2 * 100 * 4
+    assert lib.chunkft_workspace_bytes(C.byref(sp), 0, 100) == (2 * 128 + 32) * 4     # slabs of 100 -> 128 elements
     assert lib.chunkft_chunk_wgrad(C.byref(sp), 0, 100, P, 0, None, 0, None) == B.ERR_WORKSPACE
-    assert lib.chunkft_chunk_wgrad(C.byref(sp), 0, 100, P, 0, P, 799, None) == B.ERR_WORKSPACE
-    assert lib.chunkft_chunk_wgrad(C.byref(sp), 0, 100, P, 0, P + 4, 800, None) == B.ERR_WORKSPACE
+    assert lib.chunkft_chunk_wgrad(C.byref(sp), 0, 100, P, 0, P, 1151, None) == B.ERR_WORKSPACE
+    assert lib.chunkft_chunk_wgrad(C.byref(sp), 0, 100, P, 0, P + 4, 1152, None) == B.ERR_WORKSPACE
     assert lib.chunkft_wgrad_adamw_fused(C.byref(sp), 0, 100, P, P, P, P, C.byref(hp), None, 0, None) == B.ERR_WORKSPACE
     # the self-normalising kinds need 8 bytes per token for the statistics
     nm = _layer(kind=B.RMSNORM, out=1, lddy=32, norm_eps=1e-6)
@@ -201,7 +201,7 @@ def test_split_is_a_pure_function_of_shape():
     s = lib.chunkft_split_k(C.byref(small), 12345, 12345 + (2 << 20))
     assert 2 <= s <= 64
     assert lib.chunkft_split_k(C.byref(small), 12345, 12345 + (2 << 20)) == s
-    assert lib.chunkft_workspace_bytes(C.byref(small), 12345, 12345 + (2 << 20)) == s * (2 << 20) * 4
+    assert lib.chunkft_workspace_bytes(C.byref(small), 12345, 12345 + (2 << 20)) == (s * (2 << 20) + 32) * 4
     # no slab is empty: forcing more slabs than tokens allow is reduced
     tiny = _layer(T=40, split_k=8)
     assert lib.chunkft_split_k(C.byref(tiny), 0, 100) == 2      # slabs are whole 32-token tiles: 32 + 8
