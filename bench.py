@@ -476,9 +476,10 @@ def sweep(torch, B, dev, hp):
         begin = (vocab * dim - E) // 2 + 37
         end = begin + E
         layer = B.make_layer(B.EMBEDDING, ids, dY, vocab, dim)
-        g = torch.empty(E, dtype=torch.float32, device=dev)
-        master = W[begin:end].float()
-        m, v = torch.zeros_like(master), torch.zeros_like(master)
+        zero = torch.zeros((), dtype=torch.float32, device=dev)
+        g = B.chunk_array(E, begin, dev)
+        master = B.chunk_array(E, begin, dev, fill=W[begin:end].float())
+        m, v = B.chunk_array(E, begin, dev, fill=zero), B.chunk_array(E, begin, dev, fill=zero)
         h = B.hparams(step=1, **hp)
         t_w = timed(lambda: B.chunkft_chunk_wgrad(layer, begin, end, g))
         t_f = timed(lambda: B.chunkft_wgrad_adamw_fused(layer, begin, end, W, master, m, v, h))
