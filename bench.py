@@ -333,7 +333,8 @@ def streamed_state(torch, B, dev, layer, begin, end, W, h_for, ws):
 
 def block_cycle(torch, B, dev, hp):
     """One cycle over the nine tensors of a Llama-3-8B block: plan with a 256 MiB budget, then per
-    chunk one fused call per segment on one stream (a chunk may cross tensors), median of 10."""
+    chunk one fused call per segment on one stream (a chunk may cross tensors), median of 10.
+    The state of a chunk is kept as one set of arrays per segment, each in the recommended layout."""
     T = 1024
     gen = torch.Generator(device=dev)
     gen.manual_seed(211773)
@@ -359,22 +360,20 @@ def block_cycle(torch, B, dev, hp):
     _, chunks, segs = B.chunkft_plan_cycle(tensors, 256 << 20)
     h = B.hparams(step=1, **hp)
     rows = []
+    zero = torch.zeros((), dtype=torch.float32, device=dev)
     for k, (s0, s1, numel, cost) in enumerate(chunks):
-        master = torch.empty(numel, dtype=torch.float32, device=dev)
-        for (t, b, e, off) in segs[s0:s1]:
-            master[off:off + e - b] = Ws[t][b:e].float()
-        m, v = torch.zeros_like(master), torch.zeros_like(master)
+        # one set of state arrays per segment, each at the line phase of its tensor rows
         work = []
         for (t, b, e, off) in segs[s0:s1]:
             nws = B.chunkft_workspace_bytes(layers[t], b, e)
             ws = torch.empty(nws, dtype=torch.uint8, device=dev) if nws else None
-            work.append((t, b, e, off, ws))
+            state = (B.chunk_array(e - b, b, dev, fill=Ws[t][b:e].float()), B.chunk_array(e - b, b, dev, fill=zero),
+                     B.chunk_array(e - b, b, dev, fill=zero))
+            work.append((t, b, e, state, ws))
 
         def run_chunk():
-            for (t, b, e, off, ws) in work:
-                n = e - b
-                B.chunkft_wgrad_adamw_fused(layers[t], b, e, Ws[t], master[off:off + n], m[off:off + n],
-                                            v[off:off + n], h, ws=ws)
+            for (t, b, e, state, ws) in work:
+                B.chunkft_wgrad_adamw_fused(layers[t], b, e, Ws[t], state[0], state[1], state[2], h, ws=ws)
 
         for _ in range(2):
             run_chunk()
@@ -384,9 +383,20 @@ def block_cycle(torch, B, dev, hp):
             a.record(); run_chunk(); z.record(); z.synchronize()
             ts.append(a.elapsed_time(z))
         ms = sorted(ts)[len(ts) // 2]
+        alone = []
+        for (t, b, e, state, ws) in work:          # each segment by itself, back to back with itself
+            tt = []
+            for _ in range(6):
+                a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                B.chunkft_wgrad_adamw_fused(layers[t], b, e, Ws[t], state[0], state[1], state[2], h, ws=ws)
+                z.record(); z.synchronize()
+                tt.append(a.elapsed_time(z))
+            alone.append(sorted(tt)[len(tt) // 2])
         rows.append({"chunk": k, "segments": [{"tensor": shapes[t][0], "elements": e - b,
-                                               "split_k": B.chunkft_split_k(layers[t], b, e)}
-                                              for (t, b, e, off, ws) in work],
+                                               "split_k": B.chunkft_split_k(layers[t], b, e),
+                                               "ms_alone": round(alone[i], 4)}
+                                              for i, (t, b, e, state, ws) in enumerate(work)],
                      "elements": numel, "ms": round(ms, 4), "ns_per_kilo_element": round(ms * 1e6 / (numel / 1e3), 3),
                      "tflops": round(2.0 * T * numel / ms / 1e9, 1), "state_gbps": round(26.0 * numel / ms / 1e6, 1)})
     return {"T": T, "budget_MiB": 256, "tensors": [s[0] for s in shapes], "chunks": rows,

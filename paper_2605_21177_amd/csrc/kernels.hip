@@ -1367,14 +1367,17 @@ Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T
     const int64_t tiles = ceil_div(rows, bm) * ceil_div(in, bn);
     S = 1;
     const int64_t slots = kNumCU;                     // resident workgroups
-    if (mfma && tiles < slots) {
-      // One work item per CU, a single round: a second round costs more than it gains, and
-      // every further slab adds 8 bytes per element of partial traffic (measured on the
-      // lm_head shape: 4 MiB chunk 80 us with 10 slabs, 98 us with 16).
-      S = slots / tiles;
-      const int64_t max_by_len = T / 256 > 0 ? T / 256 : 1;   // keep slabs of >= 256 tokens
-      if (S > max_by_len) S = max_by_len;
-      if (S > 64) S = 64;
+    if (mfma && tiles <= slots / 4) {
+      // Splitting pays only when the tiles fill at most a quarter of the compute units, and the
+      // less the more tiles there are: every slab adds 8 bytes per element of partial traffic
+      // and the set-up and epilogue of one more work item per tile.  Measured over 16 - 192 tiles
+      // and 1024 - 8192 tokens (in = 4096): the best slab has about 512 tokens for 16 tiles,
+      // 768 for 32, 1024 for 64; more than 8 slabs never won; from 128 tiles on one slab is best.
+      // At most one work item per compute unit, a single round.
+      const int64_t kmin = tiles <= 16 ? 512 : (tiles <= 32 ? 768 : 1024);
+      S = T / kmin;
+      if (S > slots / tiles) S = slots / tiles;
+      if (S > 8) S = 8;
       if (S < 1) S = 1;
     }
   }

@@ -202,6 +202,11 @@ def test_split_is_a_pure_function_of_shape():
     assert 2 <= s <= 64
     assert lib.chunkft_split_k(C.byref(small), 12345, 12345 + (2 << 20)) == s
     assert lib.chunkft_workspace_bytes(C.byref(small), 12345, 12345 + (2 << 20)) == (s * (2 << 20) + 32) * 4
+    # a whole k / v projection at T = 1024: 64 tiles, but too few tokens for a split to pay
+    kv = _layer(out=1024, n_in=4096, T=1024, ldx=4096, lddy=1024)
+    assert lib.chunkft_split_k(C.byref(kv), 0, 1024 * 4096) == 1
+    kv8 = _layer(out=1024, n_in=4096, T=8192, ldx=4096, lddy=1024)
+    assert lib.chunkft_split_k(C.byref(kv8), 0, 1024 * 4096) == 4
     # no slab is empty: forcing more slabs than tokens allow is reduced
     tiny = _layer(T=40, split_k=8)
     assert lib.chunkft_split_k(C.byref(tiny), 0, 100) == 2      # slabs are whole 32-token tiles: 32 + 8
