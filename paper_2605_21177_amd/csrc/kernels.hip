@@ -929,6 +929,7 @@ __global__ __launch_bounds__(1024) void colsum_kernel(const WgradProblem p, cons
   const T* X = (const T*)p.X;
   float acc = 0.f;
   if (j < p.end)
+#pragma unroll 8                                   // eight tokens' loads in flight; the sum keeps its order
     for (int64_t t = tg; t < p.T; t += TG) {
       float x = load_as_f32<T>(X + t * p.ldx + j);
       if constexpr (NORM) x = (x - stats[2 * t]) * stats[2 * t + 1];
