@@ -113,6 +113,15 @@ def test_config1_standalone_adamw_elementwise():
         H.assert_elementwise(v, ref[2], 0.0, f"v step {step}")
 
 
+def test_chunk_array_has_the_phase_of_the_tensor_element():
+    for begin in (0, 1, 3, 31, 32, 13233635, 4096 * 77 + 5):
+        for n in (1, 7, 1000):
+            a = B.chunk_array(n, begin, H.DEV, fill=torch.arange(n, dtype=torch.float32))
+            assert a.numel() == n and a.dtype == torch.float32 and a.is_cuda
+            assert (a.data_ptr() // 4 - begin) % 32 == 0
+            assert torch.equal(a.cpu(), torch.arange(n, dtype=torch.float32))
+
+
 @pytest.mark.parametrize("phase", [0, 1, 3, 4, 17, 31])
 def test_standalone_adamw_at_every_array_phase(phase):
     """The element-wise pass peels up to 31 leading elements so that its 16-byte groups start on a
