@@ -529,8 +529,6 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
   // Rows / columns past the tensor are redirected to the tile's first ones (valid
   // memory, results masked in the epilogue); tokens past the end are clamped to
   // the last token and zeroed in the A fragments (mask_halves).
-  const unsigned short* ga[C::LA];
-  const unsigned short* gb[C::LB];
   const unsigned short* pa[C::LA];
   const unsigned short* pb[C::LB];
   int ka[C::LA], kb[C::LB];
@@ -544,8 +542,7 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
     int64_t r = row0 + lc * 8;
     if (r >= p.out) r = row0;
     ka[i] = k;
-    ga[i] = dY + r;
-    pa[i] = ga[i] + (k_begin + k) * p.lddy;
+    pa[i] = dY + r + (k_begin + k) * p.lddy;
   }
 #pragma unroll
   for (int i = 0; i < C::LB; ++i) {
@@ -554,8 +551,7 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
     int64_t cc = col0 + lc * 8;
     if (cc >= p.in) cc = col0;
     kb[i] = k;
-    gb[i] = X + cc;
-    pb[i] = gb[i] + (k_begin + k) * p.ldx;
+    pb[i] = X + cc + (k_begin + k) * p.ldx;
   }
   const int64_t stepA = (int64_t)C::BK * p.lddy, stepB = (int64_t)C::BK * p.ldx;
   int next_fetch = 0;   // slab index the pointers stand at
@@ -570,22 +566,20 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
   const bool has_edge = (C::WM == 2 ? tile_m == 0 : tile_m < 2) && (q.lead_base >= 0 || q.trail_row >= 0);
   const int edge_blk = C::WM == 2 ? (wave >> 2) : tile_m;
   const int ke = lane >> 1;
-  const unsigned short* ge;
+  const unsigned short* pe;
   {
     const int64_t lead = q.lead_base >= 0 ? q.lead_base : q.rb0;
     const int64_t trail = q.trail_row >= 0 ? (q.trail_row & ~(int64_t)7) : q.rb0;
-    ge = dY + ((lane & 1) ? trail : lead);
+    pe = dY + ((lane & 1) ? trail : lead) + (k_begin + ke) * p.lddy;
   }
-  const unsigned short* pe = ge + (k_begin + ke) * p.lddy;
   auto issue_edge = [&](auto stagec) {
     constexpr int STAGE = decltype(stagec)::value;
     const int stage = STAGE >= 0 ? STAGE : next_fetch % C::NS;
     const bool ragged = STAGE >= 0 ? false : (next_fetch + 1) * C::BK > klen;
     const unsigned short* src = pe;
-    if (ragged) {
-      int64_t t = k_begin + (int64_t)next_fetch * C::BK + ke;
-      if (t > p.T - 1) t = p.T - 1;
-      src = ge + t * p.lddy;
+    if (ragged) {      // the pointer stands at this slab: a token past the end steps back to the last one
+      const int64_t over = k_begin + (int64_t)next_fetch * C::BK + ke - (p.T - 1);
+      if (over > 0) src = pe - over * p.lddy;
     }
     const unsigned dst = lds_base + stage * C::STAGE_BYTES + C::A_BYTES + C::B_BYTES;
     __builtin_amdgcn_global_load_lds((GLB_PTR(const void))src, (LDS_PTR(void))(uintptr_t)dst, 16, 0, 0);
@@ -602,9 +596,8 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
       constexpr int i = idx;
       const unsigned short* src = pa[i];
       if (ragged) {
-        int64_t t = k_begin + (int64_t)next_fetch * C::BK + ka[i];
-        if (t > p.T - 1) t = p.T - 1;
-        src = ga[i] + t * p.lddy;
+        const int64_t over = k_begin + (int64_t)next_fetch * C::BK + ka[i] - (p.T - 1);
+        if (over > 0) src = pa[i] - over * p.lddy;
       }
       const unsigned dst = lds_base + stage * C::STAGE_BYTES + (wave * C::LA + i) * 1024;
       __builtin_amdgcn_global_load_lds((GLB_PTR(const void))src, (LDS_PTR(void))(uintptr_t)dst, 16, 0, 0);
@@ -613,9 +606,8 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
       constexpr int i = idx - C::LA;
       const unsigned short* src = pb[i];
       if (ragged) {
-        int64_t t = k_begin + (int64_t)next_fetch * C::BK + kb[i];
-        if (t > p.T - 1) t = p.T - 1;
-        src = gb[i] + t * p.ldx;
+        const int64_t over = k_begin + (int64_t)next_fetch * C::BK + kb[i] - (p.T - 1);
+        if (over > 0) src = pb[i] - over * p.ldx;
       }
       const unsigned dst = lds_base + stage * C::STAGE_BYTES + C::A_BYTES + (wave * C::LB + i) * 1024;
       __builtin_amdgcn_global_load_lds((GLB_PTR(const void))src, (LDS_PTR(void))(uintptr_t)dst, 16, 0, 0);
