@@ -1361,17 +1361,16 @@ Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T
     S = 1;
     const int64_t slots = kNumCU;                     // resident workgroups
     if (mfma && tiles <= slots / 4) {
-      // Splitting pays only when the tiles fill at most a quarter of the compute units, and the
-      // less the more tiles there are: every slab adds 8 bytes per element of partial traffic
-      // and the set-up and epilogue of one more work item per tile.  Measured over 16 - 192 tiles
-      // and 1024 - 8192 tokens (in = 4096): the best slab has about 512 tokens for 16 tiles,
-      // 768 for 32, 1024 for 64; more than 8 slabs never won; from 128 tiles on one slab is best.
-      // At most one work item per compute unit, a single round.
-      const int64_t kmin = tiles <= 16 ? 512 : (tiles <= 32 ? 768 : 1024);
-      S = T / kmin;
+      // Splitting pays only when the 256 x 256 tiles fill at most a quarter of the compute units.
+      // A slab costs its tokens' share of the loop, every further slab 8 bytes per element of
+      // partial traffic plus one more set-up and epilogue per tile: time ~ a T / S + b S tiles,
+      // least at S = sqrt(a T / (b tiles)).  a / b = 1 / 12 fits the measured grid (16 - 192
+      // tiles x 1024 - 8192 tokens x 1 - 16 slabs, plain and fused call, in = 4096); more than 8
+      // slabs never won, and from 128 tiles on one slab is best.
+      S = 1;
+      while ((S + 1) * (S + 1) * 12 * tiles <= T && S < 8) ++S;
       if (S > slots / tiles) S = slots / tiles;
-      if (S > 8) S = 8;
-      if (S < 1) S = 1;
+      if (S > T / 256) S = T / 256 > 0 ? T / 256 : 1;    // never slabs of fewer than 256 tokens
     }
   }
   int64_t kslab = ceil_div(ceil_div(T, S), bk) * bk;
@@ -1423,16 +1422,13 @@ int launch_mfma_cfg(const WgradProblem& p, int mode, const Sinks& s, hipStream_t
   q.group_m = mode == EMIT_ADAMW ? 4 : 8;
   q.stagger = mode == EMIT_ADAMW ? kStaggerAdamW : 0;
   const int grid = (q.n_tile_items + 7) / 8 * 8;
-  if constexpr (C::WM == 1) {           // this tile is built for the fused call only
-    if (mode != EMIT_ADAMW) return (int)hipErrorInvalidValue;
-    return launch_mfma_mode<C, EMIT_ADAMW>(q, grid, st);
-  } else {
-    switch (mode) {
-      case EMIT_STORE: return launch_mfma_mode<C, EMIT_STORE>(q, grid, st);
-      case EMIT_ACCUM: return launch_mfma_mode<C, EMIT_ACCUM>(q, grid, st);
-      case EMIT_PARTIAL: return launch_mfma_mode<C, EMIT_PARTIAL>(q, grid, st);
-      default: return (int)hipErrorInvalidValue;
-    }
+  switch (mode) {
+    case EMIT_STORE: return launch_mfma_mode<C, EMIT_STORE>(q, grid, st);
+    case EMIT_ACCUM: return launch_mfma_mode<C, EMIT_ACCUM>(q, grid, st);
+    case EMIT_PARTIAL: return launch_mfma_mode<C, EMIT_PARTIAL>(q, grid, st);
+    default:
+      if constexpr (C::WM == 1) return launch_mfma_mode<C, EMIT_ADAMW>(q, grid, st);
+      else return (int)hipErrorInvalidValue;   // the large tile is not built with the AdamW epilogue
   }
 }
 
@@ -1440,6 +1436,11 @@ int launch_wgrad_bf16_mfma(const WgradProblem& p, int mode, const Sinks& s, void
   // The plain gradient (short epilogue) is a little faster on the large tile; the fused call,
   // whose epilogue moves 26 bytes per element, gains from two workgroups per compute unit.
   if (mode == EMIT_ADAMW) return launch_mfma_cfg<FusedCfg>(p, mode, s, (hipStream_t)stream);
+  // A segment whose large tiles would occupy at most half the compute units takes the small
+  // tile too: twice the workgroups, each element still summed over the tokens in the same order.
+  const RowSplit rs = split_rows(p);
+  const int64_t big_tiles = ceil_div(rs.rb1 - rs.rb0, MainCfg::BM) * ceil_div(p.in, MainCfg::BN) * p.S;
+  if (big_tiles <= kNumCU / 2) return launch_mfma_cfg<FusedCfg>(p, mode, s, (hipStream_t)stream);
   return launch_mfma_cfg<MainCfg>(p, mode, s, (hipStream_t)stream);
 }
 
