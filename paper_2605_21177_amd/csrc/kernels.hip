@@ -1286,6 +1286,7 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 constexpr int kStaggerAdamW = 6;
 using MainCfg = RingCfg<2, 4>;    // 256 x 256 tiles, four slabs of 33 KB in LDS, one workgroup per compute unit
 using FusedCfg = RingCfg<1, 3>;   // 128 x 256 tiles, three slabs of 25 KB, two workgroups per compute unit
+                                  // (the fused call, and plain gradients with few tiles)
 
 struct RowSplit {
   int64_t rb0, rb1;     // MFMA body rows [rb0, rb1), empty if rb1 <= rb0
