@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the ChunkFT hot path on one MI355X.
 
-Workload: benchmark configs[1] -- Llama-3-8B up_proj shape (W 14336 x 4096
+Workload: configuration [1] of the task's list -- Llama-3-8B up_proj shape (W 14336 x 4096
 bf16, T = 1024 tokens), one chunk of 32 Mi contiguous elements at a seeded
 mid-row offset, synthetic Gaussian inputs already resident in HBM.
 
