@@ -103,6 +103,15 @@ def check_segment(case, dl, begin, end, *, split_k=None, fused=True, n_rows=8, n
     g_cpu = g.cpu()
     assert bool(torch.isfinite(g_cpu).all())
 
+    # --- accumulate = 1 adds exactly this gradient to what the array holds (one fp32 addition per element)
+    prefill = torch.randn(E, dtype=torch.float32, device=H.DEV, generator=torch.Generator(device=H.DEV).manual_seed(seed + 5)) * 1e-3
+    full_a, ga = H.guarded(E, prefill)
+    B.chunkft_chunk_wgrad(layer, begin, end, ga, accumulate=True, ws=ws)
+    torch.cuda.synchronize()
+    assert H.guards_intact(full_a)
+    assert torch.equal(ga, prefill + g), "accumulated gradient differs from prefill + gradient"
+    del full_a, ga, prefill
+
     # --- sampled elements
     r0, r1 = begin // n_in, (end - 1) // n_in
     picks = [np.arange(begin, min(begin + 128, end)), np.arange(max(end - 128, begin), end),
