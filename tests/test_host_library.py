@@ -212,6 +212,28 @@ def test_split_is_a_pure_function_of_shape():
     assert lib.chunkft_split_k(C.byref(tiny), 0, 100) == 2      # slabs are whole 32-token tiles: 32 + 8
 
 
+def test_autograd_segment_argument_checks():
+    """The host side of the autograd wrapper: a segment names either a gradient buffer or a
+    complete chunk state, and an empty segment needs neither."""
+    from paper_2605_21177_amd import autograd as A
+    import torch
+    buf = torch.zeros(8)
+    hp = B.hparams(1e-4, 0.9, 0.999, 1e-8, 0.01, 1)
+    assert A.ChunkSegment(0, 0).fused is False                     # tensor not in the active chunk
+    assert A.ChunkSegment(2, 10, buf).fused is False
+    assert A.ChunkSegment(2, 10, master=buf, m=buf, v=buf, hp=hp).fused is True
+    for bad in (dict(begin=5, end=3), dict(begin=-1, end=3), dict(begin=0, end=8),
+                dict(begin=0, end=8, master=buf), dict(begin=0, end=8, g=buf, master=buf, m=buf, v=buf, hp=hp)):
+        with pytest.raises(ValueError):
+            A.ChunkSegment(bad.pop("begin"), bad.pop("end"), bad.pop("g", None), **bad)
+    seg = A.ChunkSegment(2, 10, buf)
+    seg.micro_batches = 3
+    seg.reset()
+    assert seg.micro_batches == 0
+    with pytest.raises(ValueError):
+        A.chunk_linear(torch.zeros(2, 4), torch.zeros(3, 4, requires_grad=True), None)
+
+
 def test_product_path_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2605_21177_amd")
     for dirpath, _, files in os.walk(pkg):
