@@ -383,6 +383,21 @@ def block_cycle(torch, B, dev, hp):
             a.record(); run_chunk(); z.record(); z.synchronize()
             ts.append(a.elapsed_time(z))
         ms = sorted(ts)[len(ts) // 2]
+        # the same calls replayed from a captured HIP graph (the entry points only enqueue kernels)
+        stream = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            with torch.cuda.graph(graph, stream=stream):
+                run_chunk()
+        torch.cuda.synchronize()
+        tg = []
+        for _ in range(12):
+            a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); graph.replay(); z.record(); z.synchronize()
+            tg.append(a.elapsed_time(z))
+        ms_graph = sorted(tg[2:])[len(tg[2:]) // 2]
+        del graph
         alone = []
         for (t, b, e, state, ws) in work:          # each segment by itself, back to back with itself
             tt = []
@@ -397,7 +412,8 @@ def block_cycle(torch, B, dev, hp):
                                                "split_k": B.chunkft_split_k(layers[t], b, e),
                                                "ms_alone": round(alone[i], 4)}
                                               for i, (t, b, e, state, ws) in enumerate(work)],
-                     "elements": numel, "ms": round(ms, 4), "ns_per_kilo_element": round(ms * 1e6 / (numel / 1e3), 3),
+                     "elements": numel, "ms": round(ms, 4), "ms_graph_replay": round(ms_graph, 4),
+                     "ns_per_kilo_element": round(ms * 1e6 / (numel / 1e3), 3),
                      "tflops": round(2.0 * T * numel / ms / 1e9, 1), "state_gbps": round(26.0 * numel / ms / 1e6, 1)})
     return {"T": T, "budget_MiB": 256, "tensors": [s[0] for s in shapes], "chunks": rows,
             "cycle_ms": round(sum(r["ms"] for r in rows), 4)}
