@@ -178,6 +178,15 @@ def test_bf16_ranges_with_chunk_arrays_at_the_tensor_phase(begin, end):
         _full_check(_small_bf16(n_in=288), begin, end)
 
 
+@pytest.mark.parametrize("T", [70, 96, 161])
+def test_bf16_many_tiles_take_the_large_tile(T):
+    """More than 128 tiles of 256 x 256: the plain gradient runs on the large tile, here with token
+    counts that leave a ragged last slab (70, 161) or none (96), and a range with edge rows."""
+    rng = np.random.default_rng([83, T])
+    case = WL.linear_case(rng, "many tiles", 2400, 4096, T, WL.BF16, 1e-3)
+    _full_check(case, 4096 * 3 + 77, 4096 * 2397 + 5, check_accum=True)
+
+
 @pytest.mark.parametrize("split_k", [2, 3, 4])
 def test_bf16_forced_token_split(split_k):
     case = _small_bf16(T=200)
