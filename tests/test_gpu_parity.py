@@ -196,6 +196,15 @@ def test_bf16_forced_token_split(split_k):
     assert B.chunkft_split_k(layer, begin, end) == split_k
 
 
+@pytest.mark.parametrize("begin", [288 * 2 + 33, 288 * 8 + 5, 288 * 3 + 31])
+def test_bf16_forced_token_split_with_arrays_at_the_tensor_phase(begin):
+    """The slab partials are placed in the workspace at the line phase of the array they are summed
+    into: with chunk arrays at the tensor's phase that placement starts at a non-zero offset."""
+    case = _small_bf16(n_in=288, T=200)
+    with H.phase_aligned(begin):
+        _full_check(case, begin, 288 * 519 + 1, split_k=3, warm=True, step=2)
+
+
 def test_bf16_random_shapes_and_ranges():
     """Seeded random layers (sizes that are multiples of 8, so the MFMA path takes them), token
     counts with ragged last slabs, ranges from one element to the whole tensor, with and without
