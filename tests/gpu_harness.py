@@ -92,11 +92,28 @@ def guards_intact(full: torch.Tensor) -> bool:
     return bool((full[:lead] == c).all().item() and (full[lead + n:] == c).all().item())
 
 
+_WS_FULL = {}
+
+
 def workspace_for(layer: B.Layer, begin: int, end: int):
+    """Exactly chunkft_workspace_bytes() of workspace, between canary bands (see workspace_intact)."""
     nbytes = B.chunkft_workspace_bytes(layer, begin, end)
     if nbytes == 0:
         return None
-    return torch.empty(nbytes // 4, dtype=torch.float32, device=DEV)
+    assert nbytes % 4 == 0
+    full = torch.full((nbytes // 4 + 2 * GUARD,), CANARY, dtype=torch.float32, device=DEV)
+    view = full[GUARD:GUARD + nbytes // 4]
+    _WS_FULL[view.data_ptr()] = full
+    return view
+
+
+def workspace_intact(ws) -> bool:
+    """Nothing was written outside the workspace handed out by workspace_for()."""
+    if ws is None:
+        return True
+    full = _WS_FULL.pop(ws.data_ptr())
+    c = torch.tensor(CANARY, dtype=torch.float32).item()
+    return bool((full[:GUARD] == c).all().item() and (full[-GUARD:] == c).all().item())
 
 
 def gpu_wgrad(dl: DeviceLayer, begin, end, split_k=None, accumulate_into=None):
@@ -108,6 +125,7 @@ def gpu_wgrad(dl: DeviceLayer, begin, end, split_k=None, accumulate_into=None):
     B.chunkft_chunk_wgrad(layer, begin, end, g, accumulate=accumulate_into is not None, ws=ws)
     torch.cuda.synchronize()
     assert guards_intact(full), "chunk gradient wrote outside [0, end - begin)"
+    assert workspace_intact(ws), "wrote outside the workspace"
     return g.cpu().numpy().astype(np.float64)
 
 
@@ -123,6 +141,7 @@ def gpu_fused(dl: DeviceLayer, begin, end, W0, master0, m0, v0, hp: dict, step: 
     B.chunkft_wgrad_adamw_fused(layer, begin, end, W, master, m, v, B.hparams(step=step, **hp), ws=ws)
     torch.cuda.synchronize()
     assert guards_intact(fm) and guards_intact(fmm) and guards_intact(fv), "state written outside the chunk"
+    assert workspace_intact(ws), "wrote outside the workspace"
     Wc = None if W is None else W.cpu()
     return Wc, master.cpu().numpy(), m.cpu().numpy(), v.cpu().numpy()
 
