@@ -148,6 +148,7 @@ def check_segment(case, dl, begin, end, *, split_k=None, fused=True, n_rows=8, n
         assert abs(s_got - s_ref) <= 1e-4 * scale, f"bilinear property: {s_got} vs {s_ref} (scale {scale})"
 
     if not fused:
+        assert H.workspace_intact(ws)
         return g
 
     # --- fused call on the same range
@@ -164,6 +165,7 @@ def check_segment(case, dl, begin, end, *, split_k=None, fused=True, n_rows=8, n
                                 B.hparams(step=1, **HP), ws=ws)
     torch.cuda.synchronize()
     assert H.guards_intact(fm) and H.guards_intact(fmm) and H.guards_intact(fv)
+    assert H.workspace_intact(ws)
     W0d = W0.to(H.DEV)
     assert torch.equal(Wd[:begin].view(torch.int16), W0d[:begin].view(torch.int16))
     assert torch.equal(Wd[end:].view(torch.int16), W0d[end:].view(torch.int16))
