@@ -234,6 +234,16 @@ def test_autograd_segment_argument_checks():
         A.chunk_linear(torch.zeros(2, 4), torch.zeros(3, 4, requires_grad=True), None)
 
 
+def test_bench_refuses_more_than_one_gpu():
+    """The path has no collective: bench.py --gpus N with N > 1 exits with a message, before any GPU work."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
 def test_product_path_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2605_21177_amd")
     for dirpath, _, files in os.walk(pkg):
