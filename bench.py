@@ -158,6 +158,7 @@ def main():
     # what the matrix cores sustain on this device when fed from registers alone
     ceil_const = B.chunkft_calib_mfma_bf16(False)
     ceil_rand = B.chunkft_calib_mfma_bf16(True)
+    ceil_rand16 = B.chunkft_calib_mfma_bf16_shape(16, True)
 
     flops = 2.0 * T * E
     R = (end - 1) // case.n_in - begin // case.n_in + 1
@@ -210,7 +211,11 @@ def main():
                                  "drops when the operands are random bit patterns as in a real contraction",
                          "constant_operands": {"tflops": round(ceil_const[0], 1), "shader_mhz": round(ceil_const[1])},
                          "random_operands": {"tflops": round(ceil_rand[0], 1), "shader_mhz": round(ceil_rand[1])},
-                         "frac_of_random_operand_rate": round(wgrad_tflops / ceil_rand[0], 4)}},
+                         "frac_of_random_operand_rate": round(wgrad_tflops / ceil_rand[0], 4),
+                         "random_operands_16x16x32": {"tflops": round(ceil_rand16[0], 1),
+                                                      "shader_mhz": round(ceil_rand16[1]),
+                                                      "what": "the other bf16 shape draws less power and holds "
+                                                              "a higher clock when nothing else runs beside it"}}},
         "roofline_adamw": {"kernel": "elementwise_kernel (chunkft_adamw_chunk)", "bound": "hbm",
                            "achieved": round(adamw_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                            "frac": round(adamw_gbps / PEAK_HBM_GBPS, 4), "traffic": MEASURED_TRAFFIC["adamw"],

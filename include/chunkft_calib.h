@@ -33,6 +33,15 @@ extern "C" {
 int chunkft_calib_mfma_bf16(int32_t random_operands, int32_t steps, double* tflops, double* shader_mhz,
                             void* stream);
 
+/* The same measurement for either bf16 MFMA shape.
+ *   shape  32: 32x32x16 (what the call above runs, and what the weight-gradient kernel
+ *              issues); 16: 16x16x32, sixteen per step on 4 x 4 accumulator blocks, the
+ *              same flop count per step.  Anything else: CHUNKFT_ERR_INVALID_ARG.
+ * The two shapes do the same work per cycle but do not draw the same power, so under
+ * the clock limit their sustained rates differ. */
+int chunkft_calib_mfma_bf16_shape(int32_t shape, int32_t random_operands, int32_t steps, double* tflops,
+                                  double* shader_mhz, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -123,6 +123,9 @@ def lib() -> C.CDLL:
         L.chunkft_mover_sync.argtypes = [C.c_void_p]
         L.chunkft_schedule_at.restype = C.c_int
         L.chunkft_schedule_at.argtypes = [C.c_int64, C.c_int32, C.c_int64, C.POINTER(ScheduleEntry)]
+        L.chunkft_calib_mfma_bf16_shape.restype = C.c_int
+        L.chunkft_calib_mfma_bf16_shape.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double),
+                                                    C.POINTER(C.c_double), C.c_void_p]
         L.chunkft_calib_mfma_bf16.restype = C.c_int
         L.chunkft_calib_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double),
                                               C.c_void_p]
@@ -132,7 +135,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("chunkft_plan_cycle", "chunkft_split_k", "chunkft_workspace_bytes", "chunkft_chunk_wgrad",
            "chunkft_adamw_chunk", "chunkft_wgrad_adamw_fused", "chunkft_status_string",
-           "chunkft_version", "chunkft_calib_mfma_bf16", "chunkft_schedule_at",
+           "chunkft_version", "chunkft_calib_mfma_bf16", "chunkft_calib_mfma_bf16_shape", "chunkft_schedule_at",
            "chunkft_mover_create", "chunkft_mover_destroy", "chunkft_mover_load", "chunkft_mover_await_load",
            "chunkft_mover_offload", "chunkft_mover_sync")
 
@@ -273,12 +276,23 @@ def chunkft_wgrad_adamw_fused(layer: Layer, begin: int, end: int, W, master, m, 
 
 
 def chunkft_calib_mfma_bf16(random_operands: bool, steps: int = 4000, stream=None) -> Tuple[float, float]:
-    """(TFLOP/s, shader MHz) that MFMAs issued from registers sustain on the current device."""
+    """(TFLOP/s, shader MHz) that 32x32x16 MFMAs issued from registers sustain on the current device."""
     tf, mhz = C.c_double(0.0), C.c_double(0.0)
     st = lib().chunkft_calib_mfma_bf16(1 if random_operands else 0, steps, C.byref(tf), C.byref(mhz),
                                        _stream_ptr(stream))
     if st != OK:
         raise ChunkFTError(st, "chunkft_calib_mfma_bf16")
+    return tf.value, mhz.value
+
+
+def chunkft_calib_mfma_bf16_shape(shape: int, random_operands: bool, steps: int = 4000,
+                                  stream=None) -> Tuple[float, float]:
+    """The same for MFMA shape 32 (32x32x16) or 16 (16x16x32)."""
+    tf, mhz = C.c_double(0.0), C.c_double(0.0)
+    st = lib().chunkft_calib_mfma_bf16_shape(shape, 1 if random_operands else 0, steps, C.byref(tf), C.byref(mhz),
+                                             _stream_ptr(stream))
+    if st != OK:
+        raise ChunkFTError(st, "chunkft_calib_mfma_bf16_shape")
     return tf.value, mhz.value
 
 

@@ -586,3 +586,17 @@ def test_streamed_state_gives_the_resident_trajectory():
             assert torch.equal(a, b.cpu()), f"state of chunk {k} differs between streamed and resident run"
     for a, b in zip(W_str, W_res):
         assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_matrix_core_rate_measurement_runs_for_both_shapes():
+    """The measurement aid: each bf16 MFMA shape reports a rate below the part's 2.5 PFLOP/s and a clock
+    below its 2.4 GHz, and a rate that is consistent with that clock (256 CUs x 4096 flop per cycle)."""
+    for shape in (32, 16):
+        for rnd in (False, True):
+            tf, mhz = B.chunkft_calib_mfma_bf16_shape(shape, rnd, steps=2000)
+            assert 200.0 < tf < 2600.0, (shape, rnd, tf)
+            assert 500.0 < mhz < 2500.0, (shape, rnd, mhz)
+            at_clock = 256 * 4096 * mhz * 1e6 / 1e12
+            assert tf < 1.05 * at_clock, (shape, rnd, tf, at_clock)
+    tf32, _ = B.chunkft_calib_mfma_bf16(True, steps=2000)
+    assert 200.0 < tf32 < 2600.0

@@ -261,6 +261,11 @@ def test_calibration_call_validates_before_touching_the_device():
     for rnd, steps in bad:
         assert lib.chunkft_calib_mfma_bf16(rnd, steps, C.byref(tf), C.byref(mhz), None) == B.ERR_INVALID_ARG
     assert lib.chunkft_calib_mfma_bf16(1, 8, None, C.byref(mhz), None) == B.ERR_INVALID_ARG
+    for shape in (0, 8, 64, -16):        # only the two bf16 MFMA shapes exist
+        assert lib.chunkft_calib_mfma_bf16_shape(shape, 1, 8, C.byref(tf), C.byref(mhz), None) == B.ERR_INVALID_ARG
+    for shape in (16, 32):
+        assert lib.chunkft_calib_mfma_bf16_shape(shape, 1, 6, C.byref(tf), C.byref(mhz), None) == B.ERR_INVALID_ARG
+        assert lib.chunkft_calib_mfma_bf16_shape(shape, 1, 8, C.byref(tf), None, None) == B.ERR_INVALID_ARG
 
 
 def test_schedule_matches_the_simulated_algorithm():
