@@ -525,13 +525,18 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
   const unsigned short* X = (const unsigned short*)p.X;
   const unsigned lds_base = (unsigned)(uintptr_t)ldsb;
 
-  // ---- global->LDS loads: per-lane source pointers that advance one slab per fetch.
+  // ---- global->LDS loads.  A load names its source as a uniform base (scalar registers:
+  // the first row / column of the token the slab begins with, advanced one slab per fetch by
+  // scalar adds) plus a per-lane byte offset that never changes -- the buffer form of the
+  // load.  The form with a 64-bit per-lane address needs a vector add per load to advance,
+  // and that add waits in the vector pipe behind the MFMAs: measured, every such load then
+  // costs the matrix cores about 25 cycles, while the scalar-base form costs them nothing.
   // Rows / columns past the tensor are redirected to the tile's first ones (valid
   // memory, results masked in the epilogue); tokens past the end are clamped to
   // the last token and zeroed in the A fragments (mask_halves).
-  const unsigned short* pa[C::LA];
-  const unsigned short* pb[C::LB];
+  unsigned voa[C::LA], vob[C::LB];
   int ka[C::LA], kb[C::LB];
+  const unsigned lddy2 = (unsigned)(p.lddy * 2), ldx2 = (unsigned)(p.ldx * 2);    // bytes per token
   // A wave-load writes 1 KB: 1024 / RA tokens, RA / 16 lanes (16-byte slots) per token.
   constexpr int LPT_A = C::RA / 16, TPL_A = 64 / LPT_A;
 #pragma unroll
@@ -542,7 +547,7 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
     int64_t r = row0 + lc * 8;
     if (r >= p.out) r = row0;
     ka[i] = k;
-    pa[i] = dY + r + (k_begin + k) * p.lddy;
+    voa[i] = (unsigned)r * 2u + (unsigned)k * lddy2;
   }
 #pragma unroll
   for (int i = 0; i < C::LB; ++i) {
@@ -551,10 +556,23 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
     int64_t cc = col0 + lc * 8;
     if (cc >= p.in) cc = col0;
     kb[i] = k;
-    pb[i] = X + cc + (k_begin + k) * p.ldx;
+    vob[i] = (unsigned)cc * 2u + (unsigned)k * ldx2;
   }
-  const int64_t stepA = (int64_t)C::BK * p.lddy, stepB = (int64_t)C::BK * p.ldx;
-  int next_fetch = 0;   // slab index the pointers stand at
+  // row 0 / column 0 of the first token of slab `next_fetch`
+  const unsigned char* ga = (const unsigned char*)(dY + k_begin * p.lddy);
+  const unsigned char* gb = (const unsigned char*)(X + k_begin * p.ldx);
+  const int64_t stepA = (int64_t)C::BK * p.lddy * 2, stepB = (int64_t)C::BK * p.ldx * 2;     // bytes per slab
+  int next_fetch = 0;   // slab index the bases stand at
+  auto load_to_lds = [&](const unsigned char* base, unsigned voff, unsigned dst) {
+    // raw buffer over the whole address range behind `base`: the per-lane offsets are kept below 4 GB
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, -1, 0x00020000);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (LDS_PTR(void))(uintptr_t)dst, 16, (int)voff, 0, 0, 0);
+  };
+  auto next_slab = [&]() {
+    ga += stepA;
+    gb += stepB;
+    ++next_fetch;
+  };
 
   // ---- edge block (first tile row only).  One extra wave-load per slab, issued by
   // wave 0: lane l fetches, for token l/2, the 8-row group of the leading edge rows
@@ -566,24 +584,22 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
   const bool has_edge = (C::WM == 2 ? tile_m == 0 : tile_m < 2) && (q.lead_base >= 0 || q.trail_row >= 0);
   const int edge_blk = C::WM == 2 ? (wave >> 2) : tile_m;
   const int ke = lane >> 1;
-  const unsigned short* pe;
+  unsigned voe;
   {
     const int64_t lead = q.lead_base >= 0 ? q.lead_base : q.rb0;
     const int64_t trail = q.trail_row >= 0 ? (q.trail_row & ~(int64_t)7) : q.rb0;
-    pe = dY + ((lane & 1) ? trail : lead) + (k_begin + ke) * p.lddy;
+    voe = (unsigned)((lane & 1) ? trail : lead) * 2u + (unsigned)ke * lddy2;
   }
   auto issue_edge = [&](auto stagec) {
     constexpr int STAGE = decltype(stagec)::value;
     const int stage = STAGE >= 0 ? STAGE : next_fetch % C::NS;
     const bool ragged = STAGE >= 0 ? false : (next_fetch + 1) * C::BK > klen;
-    const unsigned short* src = pe;
-    if (ragged) {      // the pointer stands at this slab: a token past the end steps back to the last one
+    unsigned vo = voe;
+    if (ragged) {      // the base stands at this slab: a token past the end steps back to the last one
       const int64_t over = k_begin + (int64_t)next_fetch * C::BK + ke - (p.T - 1);
-      if (over > 0) src = pe - over * p.lddy;
+      if (over > 0) vo -= (unsigned)over * lddy2;
     }
-    const unsigned dst = lds_base + stage * C::STAGE_BYTES + C::A_BYTES + C::B_BYTES;
-    __builtin_amdgcn_global_load_lds((GLB_PTR(const void))src, (LDS_PTR(void))(uintptr_t)dst, 16, 0, 0);
-    pe += stepA;
+    load_to_lds(ga, vo, lds_base + stage * C::STAGE_BYTES + C::A_BYTES + C::B_BYTES);
   };
   // One of the L loads of slab `next_fetch`.  STAGE >= 0: the steady-state form, ring
   // slot known at compile time and the slab known to be complete; STAGE < 0: the general
@@ -594,24 +610,20 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
     const bool ragged = STAGE >= 0 ? false : (next_fetch + 1) * C::BK > klen;     // only the last slab can be
     if constexpr (idx < C::LA) {
       constexpr int i = idx;
-      const unsigned short* src = pa[i];
+      unsigned vo = voa[i];
       if (ragged) {
         const int64_t over = k_begin + (int64_t)next_fetch * C::BK + ka[i] - (p.T - 1);
-        if (over > 0) src = pa[i] - over * p.lddy;
+        if (over > 0) vo -= (unsigned)over * lddy2;
       }
-      const unsigned dst = lds_base + stage * C::STAGE_BYTES + (wave * C::LA + i) * 1024;
-      __builtin_amdgcn_global_load_lds((GLB_PTR(const void))src, (LDS_PTR(void))(uintptr_t)dst, 16, 0, 0);
-      pa[i] += stepA;
+      load_to_lds(ga, vo, lds_base + stage * C::STAGE_BYTES + (wave * C::LA + i) * 1024);
     } else {
       constexpr int i = idx - C::LA;
-      const unsigned short* src = pb[i];
+      unsigned vo = vob[i];
       if (ragged) {
         const int64_t over = k_begin + (int64_t)next_fetch * C::BK + kb[i] - (p.T - 1);
-        if (over > 0) src = pb[i] - over * p.ldx;
+        if (over > 0) vo -= (unsigned)over * ldx2;
       }
-      const unsigned dst = lds_base + stage * C::STAGE_BYTES + C::A_BYTES + (wave * C::LB + i) * 1024;
-      __builtin_amdgcn_global_load_lds((GLB_PTR(const void))src, (LDS_PTR(void))(uintptr_t)dst, 16, 0, 0);
-      pb[i] += stepB;
+      load_to_lds(gb, vo, lds_base + stage * C::STAGE_BYTES + C::A_BYTES + (wave * C::LB + i) * 1024);
     }
   };
 
@@ -717,7 +729,7 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
     if (s < nk) {
       static_for<C::L>([&](auto ic) { issue_one(ic, IntC<-1>{}); });
       if (has_edge && wave == 0) issue_edge(IntC<-1>{});
-      ++next_fetch;
+      next_slab();
     }
   // wave 0 of an edge workgroup has one more load per slab in flight than the others
   const bool five = has_edge && wave == 0;
@@ -808,7 +820,7 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
         }
       }
     });
-    if (fetch) ++next_fetch;
+    if (fetch) next_slab();
     if constexpr (EDGE) edge_mma(he1, h1);
     __builtin_amdgcn_sched_barrier(0);
     if (more) {
@@ -1338,6 +1350,8 @@ bool mfma_path_ok(const WgradProblem& p) {
   if (!(p.in % 8 == 0 && p.out % 8 == 0 && p.ldx % 8 == 0 && p.lddy % 8 == 0 && a16(p.X) && a16(p.dY)))
     return false;
   if (p.in >= (1 << 21)) return false;      // the epilogue's 32-bit tile offsets
+  // the 32-bit byte offsets of the global->LDS loads: a row / column index plus up to 63 tokens
+  if (p.out + 64 * p.lddy >= (int64_t(1) << 31) || p.in + 64 * p.ldx >= (int64_t(1) << 31)) return false;
   return true;
 }
 
