@@ -297,7 +297,6 @@ __global__ __launch_bounds__(kEdgeThreads) void wgrad_edge_kernel(const EdgePara
   }
 }
 
-#define GLB_PTR(T) __attribute__((address_space(1))) T*
 
 // LDS transpose read issued as opaque assembly: the compiler must not know that
 // it reads LDS, or it would wait for every outstanding global->LDS load before
@@ -460,13 +459,13 @@ __device__ __forceinline__ void tile_epilogue(const MfmaParams& q, unsigned char
 // Data movement.  dY and X are [token][row] / [token][column]: both operands have
 // the contraction index outermost, the opposite of what an MFMA lane wants (8
 // consecutive tokens of one row).  A slab of 32 tokens x 256 rows is copied as it
-// is (512 B per token) into LDS by global_load_lds_dwordx4 -- no VGPR staging, up
+// is (512 B per token) into LDS by buffer_load_dwordx4 ... lds -- no VGPR staging, up
 // to NS-1 slabs in flight -- and transposed on the way out by ds_read_b64_tr_b16.
 // A wave-load writes 1 KB = tokens 2j, 2j+1; lane l lands in token 2j + l/32,
 // physical 16-byte slot l%32.  To keep the 8 tokens that one transpose read
 // touches on different banks, slot s of token k holds logical slot
 // s ^ (sw(k) << 2), sw(k) = (k & 3) | ((k >> 3 & 1) << 2): the swizzle is applied
-// to the GLOBAL address each lane fetches, LDS writes stay linear.
+// to the source offset each lane fetches from, LDS writes stay linear.
 //
 // Schedule.  Per 32-token slab a wave issues 16 MFMAs in two 16-token steps.
 // The transpose reads of the NEXT step are issued behind the first three MFMAs

@@ -260,6 +260,30 @@ def test_bf16_strided_operands():
     assert H.rel_frobenius(g.cpu().numpy(), g_ref) <= 3e-3 and H.guards_intact(full)
 
 
+@pytest.mark.parametrize("log2_stride", [24, 25])
+def test_bf16_very_large_row_strides(log2_stride):
+    """The global->LDS loads address a lane's data as a 32-bit byte offset from a per-slab base: a dY row
+    stride of 2^24 elements (offsets up to 2^30 bytes) stays on the MFMA path, one of 2^25 is beyond what
+    the library accepts for it and takes the FMA kernel; both must give the gradient."""
+    rng = np.random.default_rng(83 + log2_stride)
+    out, n_in, T = 264, 136, 40 if log2_stride == 24 else 3
+    case = WL.linear_case(rng, "wide-stride", out, n_in, T, WL.BF16, 1e-3)
+    ld = (1 << log2_stride) + 8
+    dYw = torch.zeros(T, ld, dtype=torch.bfloat16, device=H.DEV)
+    dYw[:, :out] = case.dY.to(H.DEV)
+    dYw[:, out:out + 64] = 99.0          # must never be read into a result
+    X = case.X.to(H.DEV)
+    layer = B.make_layer(B.LINEAR, X, dYw[:, :out], out, n_in)
+    assert layer.lddy == ld
+    begin, end = 136 * 3 + 7, 136 * 260 + 3
+    full, g = H.guarded(end - begin)
+    B.chunkft_chunk_wgrad(layer, begin, end, g)
+    torch.cuda.synchronize()
+    g_ref = O.chunk_wgrad(WL.as_f64(case.X), WL.as_f64(case.dY), begin, end)
+    assert H.rel_frobenius(g.cpu().numpy(), g_ref) <= 3e-3 and H.guards_intact(full)
+    del dYw
+
+
 def test_vector_kind():
     rng = np.random.default_rng(80)
     for dtype in (WL.BF16, WL.F32):
