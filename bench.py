@@ -277,7 +277,8 @@ def plan_sweep(B):
     budgets = [("%d chunks" % K, -(-total_cost // K) + (-(-(-total_cost // K))) % 18) for K in (7, 32, 100)]
     budgets += [("%d GiB" % gib, gib << 30) for gib in (1, 2, 4, 8)]
     for label, budget in budgets:
-        for name, flags in (("greedy", B.PLAN_TRAINING_COST), ("balanced", B.PLAN_TRAINING_COST | B.PLAN_BALANCED)):
+        for name, flags in (("greedy", B.PLAN_TRAINING_COST), ("balanced", B.PLAN_TRAINING_COST | B.PLAN_BALANCED),
+                            ("greedy, cuts between groups of 8 rows", B.PLAN_TRAINING_COST | B.PLAN_ROWS8)):
             _, chunks, _ = B.chunkft_plan_cycle(tensors, budget, flags)
             rows.append({"budget": label, "planner": name, **stats([c[3] for c in chunks])})
     # layer-wise partition: embedding | each decoder layer | final norm + head

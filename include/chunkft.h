@@ -106,6 +106,15 @@ typedef struct {
  * suffice, so every chunk is close to the mean cost (byte-balance condition,
  * Appendix "Analysis of Memory Jitter"). */
 #define CHUNKFT_PLAN_BALANCED 2u
+/* Cut a tensor between rows only, in groups of 8 rows: where the open chunk cannot
+ * take the rest of a tensor it takes the largest whole number of 8-row groups that
+ * fits (none: the chunk is closed and the tensor goes on in the next one), so that
+ * every segment begins and ends on a row that is a multiple of 8 or at an end of
+ * its tensor (Section 3.1 splits large matrices along the row dimension; the
+ * multiple of 8 is what the gradient kernel can do without its edge-row path).
+ * A tensor of which not even one 8-row group fits an empty chunk is cut anywhere,
+ * as without the flag.  Chunks may stay below the budget by up to one group. */
+#define CHUNKFT_PLAN_ROWS8 4u
 
 /*
  * tensors (host, in)   n_tensors descriptors in model order.

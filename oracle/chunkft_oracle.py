@@ -96,15 +96,24 @@ def _cost_per_element(dtype: int, training_cost: bool) -> int:
     return s + STATE_BYTES_PER_ELEMENT if training_cost else s
 
 
-def _greedy(numels: Sequence[int], costs: Sequence[int], budget: int) -> List[List[Segment]]:
+def _greedy(numels: Sequence[int], costs: Sequence[int], budget: int,
+            groups: Sequence[int] = None) -> List[List[Segment]]:
+    """groups[t] > 1: tensor t may only be cut at multiples of groups[t] elements (whole
+    groups of rows), provided an empty chunk has room for one such group; otherwise, and
+    with groups = None, it is cut at any element."""
     chunks: List[List[Segment]] = []
     cur: List[Segment] = []
     room = budget
     filled = 0  # elements already in the open chunk
     for t, (n, s) in enumerate(zip(numels, costs)):
         p = 0
+        group = groups[t] if groups is not None and groups[t] * s <= budget else 1
         while p < n:
-            take = min(n - p, room // s)
+            fits = room // s
+            if fits >= n - p:
+                take = n - p            # the rest of the tensor goes in whole
+            else:
+                take = fits - fits % group   # p is a multiple of group: so is the cut
             if take == 0:
                 # the open chunk cannot hold one more element of this tensor
                 chunks.append(cur)
@@ -120,9 +129,15 @@ def _greedy(numels: Sequence[int], costs: Sequence[int], budget: int) -> List[Li
 
 
 def plan_cycle(tensors: Sequence[Tuple[int, int, int]], budget_bytes: int,
-               training_cost: bool = False, balanced: bool = False) -> List[List[Segment]]:
+               training_cost: bool = False, balanced: bool = False,
+               rows8: bool = False) -> List[List[Segment]]:
     """tensors: (rows, cols, dtype) in model order.  Returns chunks in cycle
     order; each chunk is its ordered list of segments.
+
+    rows8: a tensor is split along its row dimension only (Section 3.1), between
+    groups of 8 rows: the open chunk takes as many whole groups as fit, and is
+    closed if not one fits.  A tensor so wide that an empty chunk cannot hold one
+    group is cut at any element.
 
     Greedy: walk the tensors in order, put as many elements as still fit the
     budget into the open chunk, close the chunk when not even one element of
@@ -141,7 +156,8 @@ def plan_cycle(tensors: Sequence[Tuple[int, int, int]], budget_bytes: int,
     for n, s in zip(numels, costs):
         if n > 0 and s > budget_bytes:
             raise ValueError("budget smaller than one element")
-    chunks = _greedy(numels, costs, budget_bytes)
+    groups = [8 * int(c) for _, c, _ in tensors] if rows8 else None
+    chunks = _greedy(numels, costs, budget_bytes, groups)
     if balanced and len(chunks) > 1:
         k = len(chunks)
         total = sum(n * s for n, s in zip(numels, costs))
@@ -149,7 +165,7 @@ def plan_cycle(tensors: Sequence[Tuple[int, int, int]], budget_bytes: int,
         b = -(-b // 4) * 4          # round up to a multiple of 4 bytes
         b = max(b, max(s for n, s in zip(numels, costs) if n > 0))
         while b < budget_bytes:
-            cand = _greedy(numels, costs, b)
+            cand = _greedy(numels, costs, b, groups)
             if len(cand) <= k:
                 return cand
             b += 4

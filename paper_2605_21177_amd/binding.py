@@ -35,6 +35,7 @@ LAYERNORM = 4
 PLAN_GREEDY = 0
 PLAN_TRAINING_COST = 1
 PLAN_BALANCED = 2
+PLAN_ROWS8 = 4
 
 
 class TensorDesc(C.Structure):

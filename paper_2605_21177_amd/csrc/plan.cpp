@@ -5,7 +5,9 @@
 // in model order, a chunk is filled until the budget cannot take one more
 // element, and a tensor that does not fit is cut at that element, so it spans
 // chunks.  The optional training cost per element is the one of Section 3.1
-// (parameter + gradient + fp32 master + two moments).  Integer arithmetic only.
+// (parameter + gradient + fp32 master + two moments).  Optionally a tensor is cut
+// between rows only (Section 3.1 splits large matrices along the row dimension), in
+// groups of 8 rows.  Integer arithmetic only.
 
 #include "chunkft.h"
 
@@ -20,6 +22,7 @@ constexpr int64_t kStateBytes = 16;  // fp32 gradient + master + m + v
 struct Costed {
   int64_t numel;
   int64_t cost;  // bytes charged per element
+  int64_t unit;  // cuts inside this tensor fall on multiples of `unit` elements (1: anywhere)
 };
 
 // One greedy pass.  With out == nullptr it only counts.
@@ -50,12 +53,16 @@ Pass greedy(const std::vector<Costed>& ts, int64_t budget, chunkft_chunk* chunks
   for (size_t t = 0; t < ts.size(); ++t) {
     int64_t pos = 0;
     const int64_t n = ts[t].numel, s = ts[t].cost;
+    // Row-aligned cuts need room for one group of rows in an empty chunk; a tensor for
+    // which this budget has none is cut anywhere.  With u > 1 every cut of this tensor
+    // is a multiple of u, so `pos` is one too.
+    const int64_t u = (ts[t].unit > 1 && ts[t].unit <= budget / s) ? ts[t].unit : 1;
     while (pos < n) {
       // Counting only, at the start of a chunk: the chunks that this tensor fills completely
       // all look alike, so they are counted in one step (a 2^60-element tensor under a small
       // budget would otherwise take 2^50 trips).
       if (!chunks && !segs && filled == 0 && room == budget) {
-        const int64_t per_chunk = budget / s;
+        const int64_t per_chunk = budget / s / u * u;
         const int64_t whole = per_chunk > 0 ? (n - pos) / per_chunk : 0;
         if (whole > 1) {
           p.n_chunks += whole - 1;
@@ -65,8 +72,9 @@ Pass greedy(const std::vector<Costed>& ts, int64_t budget, chunkft_chunk* chunks
         }
       }
       int64_t take = room / s;
-      if (take > n - pos) take = n - pos;
-      if (take == 0) {       // not one more element of this tensor fits
+      if (take >= n - pos) take = n - pos;
+      else take = take / u * u;          // the tensor is cut here: on a group boundary
+      if (take == 0) {       // not one more element (group of rows) of this tensor fits
         close_chunk();
         continue;
       }
@@ -99,7 +107,7 @@ extern "C" int chunkft_plan_cycle(const chunkft_tensor_desc* tensors, int32_t n_
   *n_segs = 0;
   if (n_tensors < 0 || (n_tensors > 0 && !tensors)) return CHUNKFT_ERR_INVALID_ARG;
   if (budget_bytes <= 0) return CHUNKFT_ERR_INVALID_ARG;
-  if (flags & ~(CHUNKFT_PLAN_TRAINING_COST | CHUNKFT_PLAN_BALANCED)) return CHUNKFT_ERR_INVALID_ARG;
+  if (flags & ~(CHUNKFT_PLAN_TRAINING_COST | CHUNKFT_PLAN_BALANCED | CHUNKFT_PLAN_ROWS8)) return CHUNKFT_ERR_INVALID_ARG;
   if (chunks_cap < 0 || segs_cap < 0) return CHUNKFT_ERR_INVALID_ARG;
   if ((chunks_cap > 0 && !chunks) || (segs_cap > 0 && !segs)) return CHUNKFT_ERR_INVALID_ARG;
 
@@ -124,7 +132,9 @@ extern "C" int chunkft_plan_cycle(const chunkft_tensor_desc* tensors, int32_t n_
       if (s > budget_bytes) return CHUNKFT_ERR_INVALID_ARG;
       if (s > max_cost) max_cost = s;
     }
-    ts[static_cast<size_t>(t)] = {n, s};
+    int64_t unit = 1;
+    if ((flags & CHUNKFT_PLAN_ROWS8) && d.cols <= kMax / 8) unit = 8 * d.cols;
+    ts[static_cast<size_t>(t)] = {n, s, unit > 0 ? unit : 1};
   }
 
   int64_t budget = budget_bytes;

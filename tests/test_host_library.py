@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 def _oracle_plan(tensors, budget, flags):
     chunks = O.plan_cycle([(r, c, d) for r, c, d, _ in tensors], budget,
                           training_cost=bool(flags & B.PLAN_TRAINING_COST),
-                          balanced=bool(flags & B.PLAN_BALANCED))
+                          balanced=bool(flags & B.PLAN_BALANCED), rows8=bool(flags & B.PLAN_ROWS8))
     segs, cks = [], []
     for ch in chunks:
         s0 = len(segs)
@@ -48,7 +48,9 @@ def test_planner_matches_oracle_block_configs():
     tensors = [(h, h, 1, 0), (kv, h, 1, 0), (kv, h, 1, 0), (h, h, 1, 0), (ff, h, 1, 0), (ff, h, 1, 0),
                (h, ff, 1, 0), (1, h, 1, 1), (1, h, 1, 1)]
     for budget in (256 << 20, 64 << 20, (100 << 20) + 2, 1 << 20, 12345678):
-        for flags in (0, 1, 2, 3):
+        for flags in (0, 1, 2, 3, 4, 5, 6, 7):
+            if (flags & 6) == 6 and budget < (64 << 20):
+                continue        # balanced search in whole groups of rows: many passes of the plain-Python planner
             if flags & 1:
                 budget_f = budget * 9
             else:
@@ -66,7 +68,7 @@ def test_planner_matches_oracle_random():
         n = int(rng.integers(0, 8))
         tensors = [(int(rng.integers(0, 40)), int(rng.integers(0, 40)), int(rng.integers(0, 2)),
                     int(rng.integers(0, 2))) for _ in range(n)]
-        flags = int(rng.integers(0, 4))
+        flags = int(rng.integers(0, 8))
         budget = int(rng.integers(20 if flags & 1 else 4, 4000))
         st, ck, sg = B.chunkft_plan_cycle(tensors, budget, flags)
         assert st == B.OK
@@ -94,6 +96,7 @@ def test_planner_count_then_fill_and_errors():
     assert lib.chunkft_plan_cycle(arr, 2, 0, 0, None, 0, C.byref(nc), None, 0, C.byref(ns)) == B.ERR_INVALID_ARG
     assert lib.chunkft_plan_cycle(arr, 2, 3, 0, None, 0, C.byref(nc), None, 0, C.byref(ns)) == B.ERR_INVALID_ARG  # < 4 B fp32
     assert lib.chunkft_plan_cycle(arr, 2, 64, 8, None, 0, C.byref(nc), None, 0, C.byref(ns)) == B.ERR_INVALID_ARG  # unknown flag
+    assert lib.chunkft_plan_cycle(arr, 2, 64, 16, None, 0, C.byref(nc), None, 0, C.byref(ns)) == B.ERR_INVALID_ARG
     assert lib.chunkft_plan_cycle(None, 2, 64, 0, None, 0, C.byref(nc), None, 0, C.byref(ns)) == B.ERR_INVALID_ARG
     bad = (B.TensorDesc * 1)(B.TensorDesc(10, 10, 5, 0))
     assert lib.chunkft_plan_cycle(bad, 1, 64, 0, None, 0, C.byref(nc), None, 0, C.byref(ns)) == B.ERR_DTYPE
@@ -106,6 +109,31 @@ def test_planner_count_then_fill_and_errors():
     assert nc.value == 0 and ns.value == 0
     st, ck, sg = B.chunkft_plan_cycle([(0, 5, 1, 0), (3, 0, 0, 0)], 64)
     assert (st, ck, sg) == (B.OK, [], [])
+
+
+def test_planner_rows8_block_boundaries_fall_on_rows_that_are_multiples_of_8():
+    """The Llama-3-8B block under budgets that force mid-tensor cuts: with the option every segment of a
+    matrix begins and ends on a row that is a multiple of 8 (or at an end of the tensor)."""
+    h, kv, ff = 4096, 1024, 14336
+    tensors = [(h, h, 1, 0), (kv, h, 1, 0), (kv, h, 1, 0), (h, h, 1, 0), (ff, h, 1, 0), (ff, h, 1, 0),
+               (h, ff, 1, 0), (1, h, 1, 1), (1, h, 1, 1)]
+    for budget in ((100 << 20) + 2, 12345678, 64 << 20):
+        st, ck, sg = B.chunkft_plan_cycle(tensors, budget, B.PLAN_ROWS8)
+        assert st == B.OK
+        st0, ck0, sg0 = B.chunkft_plan_cycle(tensors, budget, 0)
+        assert len(ck) in (len(ck0), len(ck0) + 1)        # at most one group per chunk is given up
+        for t, b, e, _ in sg:
+            r, c = tensors[t][0], tensors[t][1]
+            assert b % (8 * c) == 0 and (e % (8 * c) == 0 or e == r * c)
+        for _, _, numel, cost in ck:
+            assert cost <= budget and cost == 2 * numel
+    # a size query with astronomically many chunks is counted in one step with the option too:
+    # 2^40 rows x 1024 bf16 under 1 MiB + 100 B: 64 groups of 8 rows = 2^19 elements per chunk
+    lib = B.lib()
+    t = (B.TensorDesc * 1)(B.TensorDesc(1 << 40, 1 << 10, B.BF16, B.LINEAR))
+    nc, ns = C.c_int64(-1), C.c_int64(-1)
+    st = lib.chunkft_plan_cycle(t, 1, (1 << 20) + 100, B.PLAN_ROWS8, None, 0, C.byref(nc), None, 0, C.byref(ns))
+    assert st == B.ERR_BUFFER_TOO_SMALL and nc.value == ns.value == (1 << 50) >> 19
 
 
 def test_planner_large_counts_near_int64():

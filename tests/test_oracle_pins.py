@@ -132,6 +132,79 @@ def test_plan_balanced():
     assert sum(2 * T * (s.end - s.begin) for ch in b for s in ch) == 2 * T * total // 2
 
 
+def test_plan_rows8_golden():
+    tensors = [(20, 4, O.BF16), (3, 4, O.BF16), (10, 5, O.F32)]
+    chunks = O.plan_cycle(tensors, 150, rows8=True)
+    got = [(k, s.tensor, s.begin, s.end, s.chunk_off) for k, ch in enumerate(chunks) for s in ch]
+    want = [tuple(int(x) for x in row) for row in _rows("plan_rows8_hand_worked.txt")]
+    assert got == want
+    _check_partition(tensors, chunks)
+
+
+def test_plan_rows8_single_matrix_closed_form():
+    """One R x c matrix, any budget that holds a group of 8 rows: every chunk but the last holds
+    floor(floor(budget / size) / 8c) groups, so row r lies in chunk (r // 8) // groups_per_chunk."""
+    for R, c in ((40, 3), (64, 5), (23, 2)):
+        tensors = [(R, c, O.BF16)]
+        for budget in range(2 * 8 * c, 2 * R * c + 5):
+            chunks = O.plan_cycle(tensors, budget, rows8=True)
+            _check_partition(tensors, chunks)
+            gpc = (budget // 2) // (8 * c)
+            n_groups = -(-R // 8)
+            if budget // 2 >= R * c:
+                assert len(chunks) == 1
+                continue
+            # a tail of fewer than 8 rows counts as a group unless it still fits behind the last whole ones
+            for k, ch in enumerate(chunks):
+                assert len(ch) == 1
+                s = ch[0]
+                assert s.begin == k * gpc * 8 * c
+                assert s.begin % (8 * c) == 0 and (s.end % (8 * c) == 0 or s.end == R * c)
+                assert 2 * (s.end - s.begin) <= budget
+            assert len(chunks) in (-(-n_groups // gpc), -(-n_groups // gpc) - 1 if R % 8 else -(-n_groups // gpc))
+
+
+def test_plan_rows8_random_invariants():
+    rng = np.random.default_rng(17)
+    for _ in range(300):
+        n = int(rng.integers(1, 6))
+        tensors = [(int(rng.integers(0, 40)), int(rng.integers(0, 6)), int(rng.integers(0, 2))) for _ in range(n)]
+        budget = int(rng.integers(4, 400))
+        for tc in (False, True):
+            if tc and budget < 20:
+                continue
+            chunks = O.plan_cycle(tensors, budget, training_cost=tc, rows8=True)
+            _check_partition(tensors, chunks)
+            size = [(4 if d == O.F32 else 2) + (16 if tc else 0) for _, _, d in tensors]
+            for ch in chunks:
+                assert 0 < O.chunk_cost_bytes(ch, tensors, tc) <= budget
+                for sg in ch:
+                    r, c, _ = tensors[sg.tensor]
+                    if 8 * c * size[sg.tensor] <= budget:      # a group fits: only whole groups, or the ends
+                        assert sg.begin % (8 * c) == 0
+                        assert sg.end % (8 * c) == 0 or sg.end == r * c
+            # a chunk is closed only when not one more group (element, for tensors cut anywhere) fits
+            for k in range(len(chunks) - 1):
+                nxt = chunks[k + 1][0]
+                r, c, _ = tensors[nxt.tensor]
+                s = size[nxt.tensor]
+                step = 8 * c if 8 * c * s <= budget else 1
+                step = min(step, r * c - nxt.begin)            # a short rest may go in whole
+                assert O.chunk_cost_bytes(chunks[k], tensors, tc) + step * s > budget
+            # without the option nothing changes for tensors that are never cut
+            if all(r * c * s <= budget for (r, c, _), s in zip(tensors, size)) and len(chunks) == 1:
+                assert chunks == O.plan_cycle(tensors, budget, training_cost=tc)
+
+
+def test_plan_rows8_equals_plain_when_the_budget_is_a_whole_number_of_groups():
+    """Uniform matrices of one width, budget a multiple of a group's bytes: the plain planner's cuts
+    already fall on group boundaries, so the option changes nothing."""
+    tensors = [(32, 4, O.BF16), (16, 4, O.BF16), (48, 4, O.BF16)]
+    for groups in range(1, 14):
+        budget = groups * 8 * 4 * 2
+        assert O.plan_cycle(tensors, budget, rows8=True) == O.plan_cycle(tensors, budget)
+
+
 def test_plan_errors():
     with pytest.raises(ValueError):
         O.plan_cycle([(2, 2, O.F32)], 3)
