@@ -370,16 +370,20 @@ def _run_cycle(layers, budget, flags=0):
     return chunks, segs, Wd, masters, ms, vs
 
 
-@pytest.mark.parametrize("budget_mib_x16", [256, 64, 100])
-def test_config3_scaled_cycle(budget_mib_x16):
+@pytest.mark.parametrize("budget_mib_x16,rows8", [(256, False), (64, False), (100, False), (100, True)])
+def test_config3_scaled_cycle(budget_mib_x16, rows8):
     """The transformer block at 1/4 linear scale (1/16 of the elements), budgets
-    scaled alike (+2 bytes on the 100 MiB one to force mid-row cuts)."""
+    scaled alike (+2 bytes on the 100 MiB one to force mid-row cuts; the same budget once more
+    with cuts between groups of 8 rows only)."""
     layers = WL.config3(scale=4, T=256)
     budget = budget_mib_x16 * (1 << 20) // 16 + (2 if budget_mib_x16 == 100 else 0)
-    chunks, segs, Wd, masters, ms, vs = _run_cycle(layers, budget)
+    chunks, segs, Wd, masters, ms, vs = _run_cycle(layers, budget, B.PLAN_ROWS8 if rows8 else 0)
     # the library's plan is the oracle's plan
-    oc = O.plan_cycle([c.desc() for c in layers], budget)
+    oc = O.plan_cycle([c.desc() for c in layers], budget, rows8=rows8)
     assert [(s.tensor, s.begin, s.end, s.chunk_off) for ch in oc for s in ch] == segs
+    if rows8:
+        for (t, b, e, _) in segs:
+            assert b % (8 * layers[t].n_in) == 0 and (e % (8 * layers[t].n_in) == 0 or e == layers[t].numel)
     # every element updated exactly once: compare with one dense AdamW step per tensor
     for t, case in enumerate(layers):
         X64, dY64 = WL.as_f64(case.X), WL.as_f64(case.dY)
