@@ -618,13 +618,15 @@ def test_streamed_state_gives_the_resident_trajectory():
 
 def test_matrix_core_rate_measurement_runs_for_both_shapes():
     """The measurement aid: each bf16 MFMA shape reports a rate below the part's 2.5 PFLOP/s and a clock
-    below its 2.4 GHz, and a rate that is consistent with that clock (256 CUs x 4096 flop per cycle)."""
+    below its 2.4 GHz, and a rate that is consistent with that clock (256 CUs x 4096 flop per cycle; the
+    clock is one workgroup's sample of the last launch and moves with the power management, the rate is
+    the mean over five launches: hence the wide margin)."""
     for shape in (32, 16):
         for rnd in (False, True):
             tf, mhz = B.chunkft_calib_mfma_bf16_shape(shape, rnd, steps=2000)
             assert 200.0 < tf < 2600.0, (shape, rnd, tf)
             assert 500.0 < mhz < 2500.0, (shape, rnd, mhz)
             at_clock = 256 * 4096 * mhz * 1e6 / 1e12
-            assert tf < 1.05 * at_clock, (shape, rnd, tf, at_clock)
+            assert tf < 1.3 * at_clock, (shape, rnd, tf, at_clock)
     tf32, _ = B.chunkft_calib_mfma_bf16(True, steps=2000)
     assert 200.0 < tf32 < 2600.0
