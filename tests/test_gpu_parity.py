@@ -284,6 +284,48 @@ def test_bf16_very_large_row_strides(log2_stride):
     del dYw
 
 
+@pytest.mark.parametrize("seed", [101, 102])
+def test_bf16_random_shapes_strides_ranges_and_splits(seed):
+    """Seeded random bf16 layers: shape, row strides, token count, range (a third begin or end on a row
+    boundary) and forced token split all drawn; the plain gradient on strided operands between canaries,
+    the fused call against the full oracle, parameters outside the range untouched."""
+    rng = np.random.default_rng(seed)
+    for it in range(25):
+        out, n_in, T = int(rng.integers(1, 90)) * 8, int(rng.integers(1, 90)) * 8, int(rng.integers(1, 300))
+        case = WL.linear_case(rng, "random", out, n_in, T, WL.BF16, 1e-3)
+        padx, pady = int(rng.integers(0, 4)) * 8, int(rng.integers(0, 4)) * 8
+        Xw = torch.full((T, n_in + padx), 99.0, dtype=torch.bfloat16, device=H.DEV)
+        dYw = torch.full((T, out + pady), 99.0, dtype=torch.bfloat16, device=H.DEV)
+        Xw[:, :n_in] = case.X.to(H.DEV)
+        dYw[:, :out] = case.dY.to(H.DEV)
+        N = out * n_in
+        b = int(rng.integers(0, N))
+        e = int(rng.integers(b + 1, N + 1))
+        if rng.random() < 0.3:
+            b = (b // n_in) * n_in
+        if rng.random() < 0.3:
+            e = max(b + 1, (e // n_in) * n_in)
+        sk = int(rng.choice([0, 0, 1, 2, 3, 5]))
+        if sk > T:
+            sk = 0
+        what = f"case {it}: {out} x {n_in}, T {T}, strides +{padx} +{pady}, [{b}, {e}), split {sk}"
+        layer = B.make_layer(B.LINEAR, Xw[:, :n_in], dYw[:, :out], out, n_in, sk)
+        ws = H.workspace_for(layer, b, e)
+        full, g = H.guarded(e - b)
+        B.chunkft_chunk_wgrad(layer, b, e, g, ws=ws)
+        torch.cuda.synchronize()
+        g_ref = O.chunk_wgrad(WL.as_f64(case.X), WL.as_f64(case.dY), b, e)
+        assert H.rel_frobenius(g.cpu().numpy(), g_ref) <= 3e-3, what
+        assert H.guards_intact(full) and H.workspace_intact(ws), what
+        th0 = WL.as_f64(case.W0).reshape(-1)[b:e].astype(np.float32)
+        z = np.zeros_like(th0)
+        Wd, master, m, v = H.gpu_fused(H.DeviceLayer(case), b, e, case.W0.reshape(-1), th0, z, z, HP, 1,
+                                       sk if sk else None)
+        bits, before = WL.bits_u16(Wd), WL.bits_u16(case.W0.reshape(-1))
+        assert np.array_equal(bits[:b], before[:b]) and np.array_equal(bits[e:], before[e:]), what
+        H.check_fused_against_oracle(g_ref, th0, z, z, HP, 1, master, m, v, bits[b:e])
+
+
 def test_vector_kind():
     rng = np.random.default_rng(80)
     for dtype in (WL.BF16, WL.F32):
