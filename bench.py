@@ -444,12 +444,14 @@ def sweep(torch, B, dev, hp):
             ts.append(a.elapsed_time(b))
         return sorted(ts)[len(ts) // 2]
 
-    def one(name, out_f, in_f, T, E, dy_scale, x_scale=1.0):
+    def one(name, out_f, in_f, T, E, dy_scale, x_scale=1.0, rows8=False):
         X = (torch.randn(T, in_f, device=dev, generator=gen) * x_scale).to(torch.bfloat16)
         dY = (torch.randn(T, out_f, device=dev, generator=gen) * dy_scale).to(torch.bfloat16)
         W = (torch.randn(out_f * in_f, device=dev, generator=gen) * 0.02).to(torch.bfloat16)
         begin = (out_f * in_f - E) // 2 + 37
         begin -= 1 if begin % in_f == 0 else 0
+        if rows8:          # a chunk as the planner cuts it with CHUNKFT_PLAN_ROWS8
+            begin = begin // (8 * in_f) * (8 * in_f)
         end = begin + E
         layer = B.make_layer(B.LINEAR, X, dY, out_f, in_f)
         nws = B.chunkft_workspace_bytes(layer, begin, end)
@@ -489,6 +491,9 @@ def sweep(torch, B, dev, hp):
 
     for T in (1024, 4096, 8192):
         one("up_proj 14336x4096", 14336, 4096, T, 32 << 20, 1e-3)
+    for T in (1024, 4096, 8192):
+        one("up_proj 14336x4096, chunk between rows that are multiples of 8", 14336, 4096, T, 32 << 20, 1e-3,
+            rows8=True)
     # the same launch on all-zero operands: same instructions, same cycles, but few bits toggle
     # in the matrix cores, so the part holds a higher clock -- the size of the data-dependent
     # clock effect on this kernel (not a performance figure)

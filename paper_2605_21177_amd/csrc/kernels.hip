@@ -32,6 +32,7 @@ namespace chunkft {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 typedef float f32x4_u __attribute__((ext_vector_type(4), aligned(4)));   // 16 bytes at any dword
 typedef unsigned int u32x2_a2 __attribute__((ext_vector_type(2), aligned(2)));   // 8 bytes at any bf16
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
@@ -672,10 +673,17 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
     he[1] = lds_tr_read<off + 4 * 32>(so < 65536 ? addrE : addrE_hi);
   };
   // the edge MFMA of a wave uses one of its two B blocks
+  // (the B block is picked by value, four selects, and not by a branch around two MFMAs: the
+  // branch made the compiler keep two copies of the accumulator block and move 16 registers,
+  // behind a full MFMA latency, in every step)
   auto edge_mma = [&](const bf16x4* he, const bf16x4* h) {
     const bf16x8 fe = __builtin_shufflevector(he[0], he[1], 0, 1, 2, 3, 4, 5, 6, 7);
-    if (edge_blk == 0) acc_e = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fe, __builtin_shufflevector(h[8], h[9], 0, 1, 2, 3, 4, 5, 6, 7), acc_e, 0, 0, 0);
-    else acc_e = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fe, __builtin_shufflevector(h[10], h[11], 0, 1, 2, 3, 4, 5, 6, 7), acc_e, 0, 0, 0);
+    const u32x4_t b0 = __builtin_bit_cast(u32x4_t, __builtin_shufflevector(h[8], h[9], 0, 1, 2, 3, 4, 5, 6, 7));
+    const u32x4_t b1 = __builtin_bit_cast(u32x4_t, __builtin_shufflevector(h[10], h[11], 0, 1, 2, 3, 4, 5, 6, 7));
+    u32x4_t bs;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) bs[e] = edge_blk == 0 ? b0[e] : b1[e];
+    acc_e = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fe, __builtin_bit_cast(bf16x8, bs), acc_e, 0, 0, 0);
   };
 
   // Fragment halves: unit u < 8 is A block u/2 (tokens 0-3 | 8-11 if u is even,
