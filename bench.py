@@ -101,9 +101,11 @@ def main():
         if not aligned:
             master = W[begin:end].float()
             return master, torch.zeros_like(master), torch.zeros_like(master)
-        zero = torch.zeros((), dtype=torch.float32, device=dev)
-        return (B.chunk_array(E, begin, dev, fill=W[begin:end].float()), B.chunk_array(E, begin, dev, fill=zero),
-                B.chunk_array(E, begin, dev, fill=zero))
+        master, m, v = B.chunk_state(E, begin, dev)
+        master.copy_(W[begin:end])
+        m.zero_()
+        v.zero_()
+        return master, m, v
 
     stA = fresh_state()
     stB = fresh_state()
@@ -188,7 +190,8 @@ def main():
             "step": "plan_cycle + chunk_wgrad + adamw_chunk + wgrad_adamw_fused",
             "split_k": S,
             "chunk_arrays": "g, master, m, v at the 128-byte phase of the tensor rows (element i of an array "
-                            "has the address phase of element begin + i of W)",
+                            "has the address phase of element begin + i of W); master, m, v cut from one "
+                            "allocation, a whole number of MiB + 256 KiB apart (binding.chunk_state)",
         },
         "wgrad": {"ms": round(ms["wgrad"], 4), "ms_median": round(ms_med["wgrad"], 4),
                   "tflops": round(wgrad_tflops, 2), "pct_mfma_peak": round(100 * wgrad_tflops / PEAK_BF16_TFLOPS, 2)},
@@ -373,8 +376,8 @@ def block_cycle(torch, B, dev, hp):
         for (t, b, e, off) in segs[s0:s1]:
             nws = B.chunkft_workspace_bytes(layers[t], b, e)
             ws = torch.empty(nws, dtype=torch.uint8, device=dev) if nws else None
-            state = (B.chunk_array(e - b, b, dev, fill=Ws[t][b:e].float()), B.chunk_array(e - b, b, dev, fill=zero),
-                     B.chunk_array(e - b, b, dev, fill=zero))
+            state = B.chunk_state(e - b, b, dev)
+            state[0].copy_(Ws[t][b:e]); state[1].zero_(); state[2].zero_()
             work.append((t, b, e, state, ws))
 
         def run_chunk():
@@ -464,8 +467,9 @@ def sweep(torch, B, dev, hp):
         sets = []
         zero = torch.zeros((), dtype=torch.float32, device=dev)
         for _ in range(n_sets):
-            sets.append((B.chunk_array(E, begin, dev, fill=W[begin:end].float()),
-                         B.chunk_array(E, begin, dev, fill=zero), B.chunk_array(E, begin, dev, fill=zero)))
+            st = B.chunk_state(E, begin, dev)
+            st[0].copy_(W[begin:end]); st[1].zero_(); st[2].zero_()
+            sets.append(st)
         h = B.hparams(step=1, **hp)
         turn = [0]
 
@@ -515,8 +519,8 @@ def sweep(torch, B, dev, hp):
         layer = B.make_layer(B.EMBEDDING, ids, dY, vocab, dim)
         zero = torch.zeros((), dtype=torch.float32, device=dev)
         g = B.chunk_array(E, begin, dev)
-        master = B.chunk_array(E, begin, dev, fill=W[begin:end].float())
-        m, v = B.chunk_array(E, begin, dev, fill=zero), B.chunk_array(E, begin, dev, fill=zero)
+        master, m, v = B.chunk_state(E, begin, dev)
+        master.copy_(W[begin:end]); m.zero_(); v.zero_()
         h = B.hparams(step=1, **hp)
         t_w = timed(lambda: B.chunkft_chunk_wgrad(layer, begin, end, g))
         t_f = timed(lambda: B.chunkft_wgrad_adamw_fused(layer, begin, end, W, master, m, v, h))

@@ -122,6 +122,23 @@ def test_chunk_array_has_the_phase_of_the_tensor_element():
             assert torch.equal(a.cpu(), torch.arange(n, dtype=torch.float32))
 
 
+def test_chunk_state_arrays_share_the_phase_and_keep_their_pitch():
+    mib = 1 << 20
+    for begin, n, count in ((0, 1, 3), (13233635, 1000, 3), (4096 * 77 + 5, (1 << 18) + 3, 4), (31, 3 << 18, 2)):
+        arrs = B.chunk_state(n, begin, H.DEV, count)
+        assert len(arrs) == count
+        for a in arrs:
+            assert a.numel() == n and a.dtype == torch.float32 and a.is_cuda
+            assert (a.data_ptr() // 4 - begin) % 32 == 0
+        for a, b in zip(arrs, arrs[1:]):
+            d = b.data_ptr() - a.data_ptr()
+            assert d >= 4 * n and d % mib == mib // 4          # a whole number of MiB plus 256 KiB, no overlap
+        for i, a in enumerate(arrs):                            # disjoint: each keeps its own values
+            a.fill_(float(i + 1))
+        for i, a in enumerate(arrs):
+            assert bool((a == float(i + 1)).all().item())
+
+
 @pytest.mark.parametrize("phase", [0, 1, 3, 4, 17, 31])
 def test_standalone_adamw_at_every_array_phase(phase):
     """The element-wise pass peels up to 31 leading elements so that its 16-byte groups start on a
