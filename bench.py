@@ -251,13 +251,8 @@ def main():
     print(json.dumps(out), flush=True)
 
 
-def plan_sweep(B):
-    """The planner on every tensor of a Llama-3-8B-shaped model in model order, with the training
-    cost per element (bf16 parameter + fp32 gradient, master, m, v = 18 B).  For each target chunk
-    count: chunks produced, the largest deviation of a chunk's cost from the mean (the imbalance
-    bound of the jitter analysis) and the jitter (max - min) / mean of the step memory 2 M + B(C_k),
-    activations left out; the same for a partition by layer, which is what layer-wise rotating
-    methods use."""
+def llama3_8b_tensors(B):
+    """Every trainable tensor of a Llama-3-8B-shaped model in model order: (rows, cols, dtype, kind)."""
     h, kv, ff, vocab, n_layers = 4096, 1024, 14336, 128256, 32
     tensors = [(vocab, h, B.BF16, B.EMBEDDING)]
     for _ in range(n_layers):
@@ -265,30 +260,46 @@ def plan_sweep(B):
                     (kv, h, B.BF16, B.LINEAR), (h, h, B.BF16, B.LINEAR), (1, h, B.BF16, B.RMSNORM),
                     (ff, h, B.BF16, B.LINEAR), (ff, h, B.BF16, B.LINEAR), (h, ff, B.BF16, B.LINEAR)]
     tensors += [(1, h, B.BF16, B.RMSNORM), (vocab, h, B.BF16, B.LINEAR)]
-    numel = [r * c for r, c, _, _ in tensors]
-    M = sum(numel)
-    total_cost = 18 * M
+    # layer-wise partition for contrast: embedding | each decoder layer | final norm + head
+    groups = [[0]] + [list(range(1 + 9 * i, 10 + 9 * i)) for i in range(n_layers)] + [[len(tensors) - 2, len(tensors) - 1]]
+    return tensors, groups
 
-    def stats(costs):
-        mean = sum(costs) / len(costs)
-        mem = [2 * M + c for c in costs]
-        return {"chunks": len(costs), "max_cost_GiB": round(max(costs) / 2 ** 30, 3),
-                "imbalance_MiB": round(max(abs(c - mean) for c in costs) / 2 ** 20, 6),
-                "jitter": round((max(mem) - min(mem)) / (sum(mem) / len(mem)), 7)}
+
+def plan_sweep(B, tensors=None, layer_groups=None, budgets=None):
+    """The planner on every tensor of a model in model order (default: Llama-3-8B shapes), with the
+    training cost per element (parameter + fp32 gradient, master, m, v).  For each budget and
+    planner variant: chunks produced, the largest deviation of a chunk's cost from the mean (the
+    imbalance of the paper's jitter analysis), the jitter (max - min) / mean of the step memory
+    2 M + B(C_k), activations left out, and the analysis' bound on it -- all four from
+    chunkft_plan_stats; the same for a partition by layer, which is what layer-wise rotating
+    methods use.  Host only."""
+    if tensors is None:
+        tensors, layer_groups = llama3_8b_tensors(B)
+    elem = {B.BF16: 2, B.F32: 4}
+    numel = [r * c for r, c, _, _ in tensors]
+    resident = sum(n * elem[d] for n, (_, _, d, _) in zip(numel, tensors))       # the 2M of the analysis
+    cost = [n * (elem[d] + 16) for n, (_, _, d, _) in zip(numel, tensors)]
+    total_cost = sum(cost)
+
+    def row(label, name, chunks):
+        st = B.chunkft_plan_stats(chunks, resident)
+        return {"budget": label, "planner": name, "chunks": st["n_chunks"], "max_cost_bytes": st["max_cost_bytes"],
+                "imbalance_bytes": st["imbalance_bytes"], "jitter": st["jitter"], "jitter_bound": st["jitter_bound"]}
 
     rows = []
-    budgets = [("%d chunks" % K, -(-total_cost // K) + (-(-(-total_cost // K))) % 18) for K in (7, 32, 100)]
-    budgets += [("%d GiB" % gib, gib << 30) for gib in (1, 2, 4, 8)]
+    if budgets is None:
+        budgets = [("%d chunks" % K, -(-total_cost // K) + (-(-(-total_cost // K))) % 18) for K in (7, 32, 100)]
+        budgets += [("%d GiB" % gib, gib << 30) for gib in (1, 2, 4, 8)]
     for label, budget in budgets:
         for name, flags in (("greedy", B.PLAN_TRAINING_COST), ("balanced", B.PLAN_TRAINING_COST | B.PLAN_BALANCED),
                             ("greedy, cuts between groups of 8 rows", B.PLAN_TRAINING_COST | B.PLAN_ROWS8)):
             _, chunks, _ = B.chunkft_plan_cycle(tensors, budget, flags)
-            rows.append({"budget": label, "planner": name, **stats([c[3] for c in chunks])})
-    # layer-wise partition: embedding | each decoder layer | final norm + head
-    layer_numel = [numel[0]] + [sum(numel[1 + 9 * i:10 + 9 * i]) for i in range(n_layers)] + [numel[-2] + numel[-1]]
-    rows.append({"budget": "-", "planner": "one partition per layer (for contrast)",
-                 **stats([18 * x for x in layer_numel])})
-    return {"model": "Llama-3-8B shapes, %d tensors, %.3f G parameters" % (len(tensors), M / 1e9), "rows": rows}
+            rows.append(row(label, name, chunks))
+    if layer_groups:
+        by_layer = [(0, 0, sum(numel[t] for t in grp), sum(cost[t] for t in grp)) for grp in layer_groups]
+        rows.append(row("-", "one partition per layer (for contrast)", by_layer))
+    return {"model": "%d tensors, %.3f G parameters, %d resident bytes" % (len(tensors), sum(numel) / 1e9, resident),
+            "rows": rows}
 
 
 def streamed_state(torch, B, dev, layer, begin, end, W, h_for, ws):

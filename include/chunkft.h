@@ -22,13 +22,18 @@
  *   - Pointers marked (device) must be device memory reachable from the
  *     current HIP device; pointers marked (host) are ordinary host memory.
  *   - The library allocates no device memory and keeps no data between
- *     calls (its only process state is a flag per kernel and device that the
- *     kernel's LDS size attribute has been set).  Every buffer is owned by the caller.
+ *     calls (its only process state is, per device, the number of compute
+ *     units and a flag per kernel that its LDS size attribute has been set).
+ *     Every buffer is owned by the caller.
  *   - Device entry points validate their arguments synchronously, then
  *     enqueue kernels on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) and return without waiting.  They return CHUNKFT_OK or
- *     a negative chunkft_status; nothing throws or aborts across this ABI,
- *     and on an error status no kernel has been enqueued.
+ *     a negative chunkft_status; nothing throws or aborts across this ABI.
+ *     On every status but CHUNKFT_ERR_HIP nothing has been enqueued and no
+ *     buffer has been touched.  CHUNKFT_ERR_HIP means the runtime refused a
+ *     launch: a call that takes several kernels (a token split, a chunk of a
+ *     few rows) may then have enqueued the earlier ones, so the outputs and
+ *     the workspace of that call are unspecified.
  *   - Identical inputs give bit-identical outputs on every call.
  */
 #ifndef CHUNKFT_H
@@ -110,8 +115,9 @@ typedef struct {
  * take the rest of a tensor it takes the largest whole number of 8-row groups that
  * fits (none: the chunk is closed and the tensor goes on in the next one), so that
  * every segment begins and ends on a row that is a multiple of 8 or at an end of
- * its tensor (Section 3.1 splits large matrices along the row dimension; the
- * multiple of 8 is what the gradient kernel can do without its edge-row path).
+ * its tensor (Section 3 "Method", first paragraph, splits large matrices along the
+ * row dimension; the multiple of 8 is what the gradient kernel can do without its
+ * edge-row path).
  * A tensor of which not even one 8-row group fits an empty chunk is cut anywhere,
  * as without the flag.  Chunks may stay below the budget by up to one group. */
 #define CHUNKFT_PLAN_ROWS8 4u
@@ -133,6 +139,33 @@ int chunkft_plan_cycle(const chunkft_tensor_desc* tensors, int32_t n_tensors,
                        int64_t budget_bytes, uint32_t flags,
                        chunkft_chunk* chunks, int64_t chunks_cap, int64_t* n_chunks,
                        chunkft_segment* segs, int64_t segs_cap, int64_t* n_segs);
+
+/* ------------------------------------------------------------------------
+ * Summary of a plan (host only)
+ *
+ * Paper: appendix "Analysis of Memory Jitter".  With the step memory of chunk k
+ * taken as M_k = resident_bytes + B(C_k) (the appendix's 2M + B(C_k), activations
+ * and temporary buffers left out) and B(C_k) = chunks[k].cost_bytes:
+ *   mean_cost_bytes  (1/K) sum_k B(C_k)
+ *   imbalance_bytes  eps_B = max_k | B(C_k) - mean |
+ *   jitter           (max_k M_k - min_k M_k) / ((1/K) sum_k M_k)
+ *   jitter_bound     2 eps_B / (resident_bytes + mean), which the appendix gives
+ *                    as the bound of the jitter (it holds exactly for this M_k).
+ * Plan with CHUNKFT_PLAN_TRAINING_COST for B to be the appendix's
+ * parameter + gradient + master + optimizer bytes; resident_bytes is then
+ * 2 bytes per parameter of the whole model for bf16 weights.
+ * ---------------------------------------------------------------------- */
+typedef struct {
+  int64_t n_chunks;
+  int64_t min_cost_bytes, max_cost_bytes;
+  double mean_cost_bytes, imbalance_bytes, jitter, jitter_bound;
+} chunkft_plan_summary;
+
+/* chunks (host, in)  n_chunks >= 1 entries as chunkft_plan_cycle wrote them (only
+ *                    cost_bytes is read, each >= 0);  resident_bytes >= 0;
+ * out (host, out).   Errors: CHUNKFT_ERR_INVALID_ARG. */
+int chunkft_plan_stats(const chunkft_chunk* chunks, int64_t n_chunks, int64_t resident_bytes,
+                       chunkft_plan_summary* out);
 
 /* ------------------------------------------------------------------------
  * Rotating schedule (host only)

@@ -49,7 +49,12 @@ What each function follows:
 * rotating_schedule     -- Algorithm 1, the loop over training steps: the active
                            index, the load / offload steps and the per-chunk
                            update counters n^(k), simulated step by step.
-* jitter / imbalance    -- Appendix F definitions.
+* jitter / imbalance / step_memory / jitter_bound
+                        -- appendix "Analysis of Memory Jitter": the jitter ratio of
+                           a sequence of step memories, the chunking imbalance
+                           epsilon_B, the step memory 2M + B(C_k) of a chunk
+                           (activations and temporary buffers left out) and the
+                           bound 2 epsilon_B / (2M + mean B) on the jitter.
 
 Pins (tests/test_oracle_pins.py): brute-force loops on tiny layers, closed
 forms of the first AdamW step, hand-worked two-step values, torch.optim.AdamW
@@ -134,8 +139,8 @@ def plan_cycle(tensors: Sequence[Tuple[int, int, int]], budget_bytes: int,
     """tensors: (rows, cols, dtype) in model order.  Returns chunks in cycle
     order; each chunk is its ordered list of segments.
 
-    rows8: a tensor is split along its row dimension only (Section 3.1), between
-    groups of 8 rows: the open chunk takes as many whole groups as fit, and is
+    rows8: a tensor is split along its row dimension only (Section 3 "Method",
+    first paragraph), between groups of 8 rows: the open chunk takes as many whole groups as fit, and is
     closed if not one fits.  A tensor so wide that an empty chunk cannot hold one
     group is cut at any element.
 
@@ -188,6 +193,19 @@ def jitter(step_memory: Sequence[float]) -> float:
     """Appendix F: (max_t M_t - min_t M_t) / mean_t M_t."""
     m = np.asarray(step_memory, dtype=np.float64)
     return float((m.max() - m.min()) / m.mean())
+
+
+def step_memory(chunks, tensors, resident_bytes: int, training_cost: bool = True) -> List[float]:
+    """Appendix F: M_k = 2M + B(C_k) + A_k + Delta_k with the activation and temporary
+    terms left out; `resident_bytes` is the 2M of the formula (the low-precision
+    parameters of the whole model, resident at every step)."""
+    return [float(resident_bytes + chunk_cost_bytes(c, tensors, training_cost)) for c in chunks]
+
+
+def jitter_bound(chunks, tensors, resident_bytes: int, training_cost: bool = True) -> float:
+    """Appendix F, last equation: 2 epsilon_B / (2M + (1/K) sum_j B(C_j))."""
+    b = np.array([chunk_cost_bytes(c, tensors, training_cost) for c in chunks], dtype=np.float64)
+    return float(2.0 * imbalance(chunks, tensors, training_cost) / (resident_bytes + b.mean()))
 
 
 # --------------------------------------------------------------------------

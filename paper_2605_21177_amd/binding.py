@@ -52,6 +52,12 @@ class Chunk(C.Structure):
                 ("cost_bytes", C.c_int64)]
 
 
+class PlanSummary(C.Structure):
+    _fields_ = [("n_chunks", C.c_int64), ("min_cost_bytes", C.c_int64), ("max_cost_bytes", C.c_int64),
+                ("mean_cost_bytes", C.c_double), ("imbalance_bytes", C.c_double), ("jitter", C.c_double),
+                ("jitter_bound", C.c_double)]
+
+
 class AdamWHparams(C.Structure):
     _fields_ = [("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
                 ("weight_decay", C.c_double), ("step", C.c_int64)]
@@ -91,6 +97,8 @@ def lib() -> C.CDLL:
         L.chunkft_plan_cycle.argtypes = [C.POINTER(TensorDesc), C.c_int32, C.c_int64, C.c_uint32,
                                          C.POINTER(Chunk), C.c_int64, C.POINTER(C.c_int64),
                                          C.POINTER(Segment), C.c_int64, C.POINTER(C.c_int64)]
+        L.chunkft_plan_stats.restype = C.c_int
+        L.chunkft_plan_stats.argtypes = [C.POINTER(Chunk), C.c_int64, C.c_int64, C.POINTER(PlanSummary)]
         L.chunkft_split_k.restype = C.c_int
         L.chunkft_split_k.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64]
         L.chunkft_workspace_bytes.restype = C.c_size_t
@@ -134,7 +142,7 @@ def lib() -> C.CDLL:
     return _lib
 
 
-EXPORTS = ("chunkft_plan_cycle", "chunkft_split_k", "chunkft_workspace_bytes", "chunkft_chunk_wgrad",
+EXPORTS = ("chunkft_plan_cycle", "chunkft_plan_stats", "chunkft_split_k", "chunkft_workspace_bytes", "chunkft_chunk_wgrad",
            "chunkft_adamw_chunk", "chunkft_wgrad_adamw_fused", "chunkft_status_string",
            "chunkft_version", "chunkft_calib_mfma_bf16", "chunkft_calib_mfma_bf16_shape", "chunkft_schedule_at",
            "chunkft_mover_create", "chunkft_mover_destroy", "chunkft_mover_load", "chunkft_mover_await_load",
@@ -177,6 +185,22 @@ def chunkft_plan_cycle(tensors: Sequence[Tuple[int, int, int, int]], budget_byte
              for i in range(nc.value)]
     out_s = [(segs[i].tensor, segs[i].begin, segs[i].end, segs[i].chunk_off) for i in range(ns.value)]
     return OK, out_c, out_s
+
+
+def chunkft_plan_stats(chunks: Sequence[Tuple[int, int, int, int]], resident_bytes: int, check: bool = True):
+    """chunks as chunkft_plan_cycle returns them.  Returns a dict with the fields of
+    chunkft_plan_summary, or the status."""
+    n = len(chunks)
+    arr = (Chunk * max(n, 1))()
+    for i, (s0, s1, numel, cost) in enumerate(chunks):
+        arr[i] = Chunk(s0, s1, numel, cost)
+    out = PlanSummary()
+    st = lib().chunkft_plan_stats(arr, n, resident_bytes, C.byref(out))
+    if st != OK:
+        if check:
+            raise ChunkFTError(st, "chunkft_plan_stats")
+        return st
+    return {name: getattr(out, name) for name, _ in PlanSummary._fields_}
 
 
 # ---------------------------------------------------------- device calls

@@ -6,11 +6,14 @@
 // element, and a tensor that does not fit is cut at that element, so it spans
 // chunks.  The optional training cost per element is the one of Section 3.1
 // (parameter + gradient + fp32 master + two moments).  Optionally a tensor is cut
-// between rows only (Section 3.1 splits large matrices along the row dimension), in
-// groups of 8 rows.  Integer arithmetic only.
+// between rows only (the same opening paragraph of Section 3 splits large matrices
+// along the row dimension), in groups of 8 rows.  Integer arithmetic only, except
+// the summary of a plan (chunkft_plan_stats: the imbalance and jitter of the paper's
+// appendix on memory jitter), which is a handful of doubles.
 
 #include "chunkft.h"
 
+#include <cmath>
 #include <cstdint>
 #include <limits>
 #include <vector>
@@ -29,6 +32,10 @@ struct Costed {
 struct Pass {
   int64_t n_chunks = 0;
   int64_t n_segs = 0;
+  // Fewest bytes by which the budget must grow before this pass takes a different decision
+  // anywhere (a cut lets one more element or group of rows in, or a tensor becomes narrow
+  // enough to be cut between rows): every budget in [budget, budget + slack) gives the same plan.
+  int64_t slack = std::numeric_limits<int64_t>::max();
 };
 
 Pass greedy(const std::vector<Costed>& ts, int64_t budget, chunkft_chunk* chunks,
@@ -57,6 +64,11 @@ Pass greedy(const std::vector<Costed>& ts, int64_t budget, chunkft_chunk* chunks
     // which this budget has none is cut anywhere.  With u > 1 every cut of this tensor
     // is a multiple of u, so `pos` is one too.
     const int64_t u = (ts[t].unit > 1 && ts[t].unit <= budget / s) ? ts[t].unit : 1;
+    if (n > 0 && ts[t].unit > 1 && u == 1 && ts[t].unit <= std::numeric_limits<int64_t>::max() / s) {
+      const int64_t d = ts[t].unit * s - budget;     // > 0: from there on the tensor is cut between rows
+      if (d < p.slack) p.slack = d;
+    }
+    const int64_t us = u * s;                        // bytes of one unit; fits: u <= budget / s
     while (pos < n) {
       // Counting only, at the start of a chunk: the chunks that this tensor fills completely
       // all look alike, so they are counted in one step (a 2^60-element tensor under a small
@@ -65,6 +77,8 @@ Pass greedy(const std::vector<Costed>& ts, int64_t budget, chunkft_chunk* chunks
         const int64_t per_chunk = budget / s / u * u;
         const int64_t whole = per_chunk > 0 ? (n - pos) / per_chunk : 0;
         if (whole > 1) {
+          const int64_t d = us - budget % us;        // each of these chunks would take one more unit
+          if (d < p.slack) p.slack = d;
           p.n_chunks += whole - 1;
           p.n_segs += whole - 1;
           pos += (whole - 1) * per_chunk;
@@ -73,7 +87,13 @@ Pass greedy(const std::vector<Costed>& ts, int64_t budget, chunkft_chunk* chunks
       }
       int64_t take = room / s;
       if (take >= n - pos) take = n - pos;
-      else take = take / u * u;          // the tensor is cut here: on a group boundary
+      else {
+        take = take / u * u;             // the tensor is cut here: on a group boundary
+        // room for one more unit, or for the whole rest (whose last group may be short), changes the cut
+        const int64_t d_unit = us - room % us, d_rest = (n - pos) * s - room;
+        const int64_t d = d_unit < d_rest ? d_unit : d_rest;
+        if (d < p.slack) p.slack = d;
+      }
       if (take == 0) {       // not one more element (group of rows) of this tensor fits
         close_chunk();
         continue;
@@ -144,10 +164,17 @@ extern "C" int chunkft_plan_cycle(const chunkft_tensor_desc* tensors, int32_t n_
     int64_t b = total / k + (total % k ? 1 : 0);
     b = (b + 3) / 4 * 4;
     if (b < max_cost) b = max_cost;
-    // b <= budget_bytes always terminates the search: greedy(budget_bytes) needs k chunks
-    for (;; b += 4) {
-      if (b >= budget_bytes) { b = budget_bytes; break; }
-      if (greedy(ts, b, nullptr, nullptr).n_chunks <= k) break;
+    // The candidates are b, b + 4, b + 8, ... below the caller's budget, the answer the first
+    // one that needs no more than k chunks.  A pass also tells how far the budget can grow
+    // before anything in it changes, so the candidates in between are skipped, not tried:
+    // a handful of passes where cuts between groups of rows put megabytes between two plans.
+    for (;;) {
+      if (b >= budget_bytes) { b = budget_bytes; break; }   // greedy(budget_bytes) needs k chunks
+      const Pass trial = greedy(ts, b, nullptr, nullptr);
+      if (trial.n_chunks <= k) break;
+      const int64_t grow = trial.slack > 0 ? trial.slack : 1;
+      if (grow >= budget_bytes - b) { b = budget_bytes; break; }
+      b += (grow + 3) / 4 * 4;
     }
     budget = b;
     need = greedy(ts, budget, nullptr, nullptr);
@@ -178,5 +205,36 @@ extern "C" int chunkft_schedule_at(int64_t step, int32_t n_chunks, int64_t inter
   out->load_before = within == 0;
   out->offload_after = within == interval - 1;
   out->reserved = 0;
+  return CHUNKFT_OK;
+}
+
+// Summary of a plan in the terms of the paper's appendix on memory jitter: with the step memory
+// M_k = resident + B(C_k) (activations and temporaries left out), the mean chunk cost, the
+// imbalance eps_B = max_k |B(C_k) - mean|, the jitter (max_k M_k - min_k M_k) / mean_k M_k and
+// the bound 2 eps_B / (resident + mean) that the appendix gives for it.
+extern "C" int chunkft_plan_stats(const chunkft_chunk* chunks, int64_t n_chunks, int64_t resident_bytes,
+                                  chunkft_plan_summary* out) {
+  if (!chunks || !out || n_chunks < 1 || resident_bytes < 0) return CHUNKFT_ERR_INVALID_ARG;
+  int64_t lo = std::numeric_limits<int64_t>::max(), hi = 0;
+  long double sum = 0.0L;
+  for (int64_t k = 0; k < n_chunks; ++k) {
+    const int64_t c = chunks[k].cost_bytes;
+    if (c < 0) return CHUNKFT_ERR_INVALID_ARG;
+    if (c < lo) lo = c;
+    if (c > hi) hi = c;
+    sum += static_cast<long double>(c);
+  }
+  const long double mean = sum / static_cast<long double>(n_chunks);
+  // |B - mean| is largest at one of the two extremes
+  const long double up = static_cast<long double>(hi) - mean, down = mean - static_cast<long double>(lo);
+  const long double eps_b = up > down ? up : down;
+  const long double mean_mem = static_cast<long double>(resident_bytes) + mean;
+  out->n_chunks = n_chunks;
+  out->min_cost_bytes = lo;
+  out->max_cost_bytes = hi;
+  out->mean_cost_bytes = static_cast<double>(mean);
+  out->imbalance_bytes = static_cast<double>(eps_b);
+  out->jitter = mean_mem > 0.0L ? static_cast<double>(static_cast<long double>(hi - lo) / mean_mem) : 0.0;
+  out->jitter_bound = mean_mem > 0.0L ? static_cast<double>(2.0L * eps_b / mean_mem) : 0.0;
   return CHUNKFT_OK;
 }

@@ -76,6 +76,98 @@ def test_planner_matches_oracle_random():
         assert (ck, sg) == (want_ck, want_sg)
 
 
+def test_plan_stats_match_the_oracle_and_the_hand_worked_case():
+    """chunkft_plan_stats against the oracle's imbalance / jitter / bound (appendix "Analysis of
+    Memory Jitter") on planner output, and on the three-chunk case worked by hand under
+    tests/golden/.  Floating point on both sides: compared to 1e-12 relative."""
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        n = int(rng.integers(1, 7))
+        tensors = [(int(rng.integers(1, 40)), int(rng.integers(1, 40)), int(rng.integers(0, 2)), 0) for _ in range(n)]
+        flags = int(rng.integers(0, 8))
+        tc = bool(flags & B.PLAN_TRAINING_COST)
+        budget = int(rng.integers(20 if tc else 4, 4000))
+        _, ck, _ = B.chunkft_plan_cycle(tensors, budget, flags)
+        t3 = [(r, c, d) for r, c, d, _ in tensors]
+        want = O.plan_cycle(t3, budget, training_cost=tc, balanced=bool(flags & 2), rows8=bool(flags & 4))
+        resident = int(rng.integers(0, 10000))
+        got = B.chunkft_plan_stats(ck, resident)
+        costs = [O.chunk_cost_bytes(c, t3, tc) for c in want]
+        assert got["n_chunks"] == len(want) and got["min_cost_bytes"] == min(costs) and got["max_cost_bytes"] == max(costs)
+        np.testing.assert_allclose(got["mean_cost_bytes"], sum(costs) / len(costs), rtol=1e-12)
+        np.testing.assert_allclose(got["imbalance_bytes"], O.imbalance(want, t3, tc), rtol=1e-12, atol=1e-9)
+        np.testing.assert_allclose(got["jitter"], O.jitter(O.step_memory(want, t3, resident, tc)), rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(got["jitter_bound"], O.jitter_bound(want, t3, resident, tc), rtol=1e-12, atol=1e-15)
+        assert got["jitter"] <= got["jitter_bound"] * (1 + 1e-12)
+    for row in open(os.path.join(ROOT, "tests", "golden", "jitter_three_chunks_hand_worked.txt")):
+        if row.startswith("#") or not row.strip():
+            continue
+        f = [int(x) for x in row.split()]
+        got = B.chunkft_plan_stats([(0, 1, 0, f[1]), (1, 2, 0, f[2]), (2, 3, 0, f[3])], 90)
+        assert got["mean_cost_bytes"] == f[4] and got["imbalance_bytes"] == f[5]
+        assert got["jitter"] == f[6] / f[7] and got["jitter_bound"] == f[8] / f[9]
+    assert B.chunkft_plan_stats([], 0, check=False) == B.ERR_INVALID_ARG
+    assert B.chunkft_plan_stats([(0, 1, 1, 2)], -1, check=False) == B.ERR_INVALID_ARG
+    assert B.chunkft_plan_stats([(0, 1, 1, -2)], 0, check=False) == B.ERR_INVALID_ARG
+    lib = B.lib()
+    assert lib.chunkft_plan_stats(None, 1, 0, C.byref(B.PlanSummary())) == B.ERR_INVALID_ARG
+    assert lib.chunkft_plan_stats((B.Chunk * 1)(), 1, 0, None) == B.ERR_INVALID_ARG
+
+
+def test_bench_plan_sweep_reports_the_oracle_numbers():
+    """bench.py --plan-sweep on a small tensor list: every row's chunk count, imbalance, jitter and
+    bound equal what the oracle's planner and its jitter functions give for the same budget."""
+    import bench
+    tensors = [(50, 16, B.BF16, B.EMBEDDING), (1, 16, B.BF16, B.RMSNORM), (16, 16, B.BF16, B.LINEAR),
+               (40, 16, B.F32, B.LINEAR), (16, 40, B.BF16, B.LINEAR), (1, 16, B.BF16, B.RMSNORM), (50, 16, B.BF16, B.LINEAR)]
+    groups = [[0], [1, 2, 3, 4], [5, 6]]
+    budgets = [("a", 9000), ("b", 20001), ("c", 3 * 18 * 128)]
+    out = bench.plan_sweep(B, tensors, groups, budgets)
+    t3 = [(r, c, d) for r, c, d, _ in tensors]
+    resident = sum(r * c * (4 if d == B.F32 else 2) for r, c, d in t3)
+    rows = iter(out["rows"])
+    for _, budget in budgets:
+        for kw in (dict(), dict(balanced=True), dict(rows8=True)):
+            want = O.plan_cycle(t3, budget, training_cost=True, **kw)
+            row = next(rows)
+            assert row["chunks"] == len(want)
+            assert row["max_cost_bytes"] == max(O.chunk_cost_bytes(c, t3, True) for c in want)
+            np.testing.assert_allclose(row["imbalance_bytes"], O.imbalance(want, t3, True), rtol=1e-12, atol=1e-9)
+            np.testing.assert_allclose(row["jitter"], O.jitter(O.step_memory(want, t3, resident, True)), rtol=1e-12, atol=1e-15)
+            np.testing.assert_allclose(row["jitter_bound"], O.jitter_bound(want, t3, resident, True), rtol=1e-12, atol=1e-15)
+    # the layer-wise partition: one "chunk" per group of tensors, whole tensors only
+    by_layer = [[O.Segment(t, 0, t3[t][0] * t3[t][1], 0) for t in grp] for grp in groups]
+    row = next(rows)
+    assert row["chunks"] == 3
+    np.testing.assert_allclose(row["imbalance_bytes"], O.imbalance(by_layer, t3, True), rtol=1e-12)
+    np.testing.assert_allclose(row["jitter"], O.jitter(O.step_memory(by_layer, t3, resident, True)), rtol=1e-12)
+
+
+def test_balanced_search_is_quick_where_cuts_fall_between_row_groups():
+    """Balanced + row groups on the Llama-3-8B block: two candidate capacities can lie a whole group of
+    rows (megabytes) apart; the search skips the capacities that cannot change the plan instead of
+    trying each multiple of 4 bytes.  The result is still the first capacity (in steps of 4 bytes from
+    ceil(total / K)) that needs no more than K chunks: checked against a direct scan of the last
+    kilobyte before it."""
+    import time
+    h, kv, ff = 4096, 1024, 14336
+    tensors = [(h, h, 1, 0), (kv, h, 1, 0), (kv, h, 1, 0), (h, h, 1, 0), (ff, h, 1, 0), (ff, h, 1, 0),
+               (h, ff, 1, 0), (1, h, 1, 1), (1, h, 1, 1)]
+    for budget in (12345678, (100 << 20) + 2, 9 * 12345678):
+        flags = B.PLAN_BALANCED | B.PLAN_ROWS8 | (B.PLAN_TRAINING_COST if budget > (1 << 27) else 0)
+        t0 = time.perf_counter()
+        _, ck, sg = B.chunkft_plan_cycle(tensors, budget, flags)
+        assert time.perf_counter() - t0 < 2.0
+        _, ck0, _ = B.chunkft_plan_cycle(tensors, budget, flags & ~B.PLAN_BALANCED)
+        assert len(ck) <= len(ck0) and all(c[3] <= budget for c in ck)
+        cap = max(c[3] for c in ck)
+        # the plan is the greedy plan of some capacity b >= cap; no capacity in the kilobyte below cap
+        # (same residue mod 4 as the search's candidates or not) manages with as few chunks
+        for b in range(max(cap - 1024, 20), cap):
+            _, ckb, _ = B.chunkft_plan_cycle(tensors, b, flags & ~B.PLAN_BALANCED)
+            assert len(ckb) > len(ck0) or max(c[3] for c in ckb) >= cap or len(ckb) > len(ck)
+
+
 def test_planner_count_then_fill_and_errors():
     lib = B.lib()
     arr = (B.TensorDesc * 2)(B.TensorDesc(10, 10, 1, 0), B.TensorDesc(1, 7, 0, 1))

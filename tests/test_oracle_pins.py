@@ -117,6 +117,110 @@ def test_plan_training_cost_scales_budget():
         assert a == b
 
 
+def test_imbalance_and_jitter_hand_worked():
+    """Appendix "Analysis of Memory Jitter": eps_B, the step memory 2M + B(C_k), the jitter
+    ratio and its bound on a three-chunk plan whose numbers are worked by hand in the fixture.
+    max - min (50) or the deviation from the median (40) instead of eps_B = 30 fail here."""
+    tensors = [(1, 45, O.BF16)]
+    chunks = [[O.Segment(0, 0, 5, 0)], [O.Segment(0, 5, 15, 0)], [O.Segment(0, 15, 45, 0)]]
+    _check_partition(tensors, chunks)
+    resident = 2 * 45
+    for row in _rows("jitter_three_chunks_hand_worked.txt"):
+        tc = bool(int(row[0]))
+        b = [int(x) for x in row[1:4]]
+        mean, eps, jn, jd, bn, bd = (int(x) for x in row[4:10])
+        assert [O.chunk_cost_bytes(c, tensors, tc) for c in chunks] == b
+        assert O.imbalance(chunks, tensors, tc) == float(eps)
+        mem = O.step_memory(chunks, tensors, resident, tc)
+        assert mem == [float(resident + x) for x in b] and sum(mem) / 3 == jd
+        assert O.jitter(mem) == jn / jd
+        assert O.jitter_bound(chunks, tensors, resident, tc) == bn / bd
+    # a single chunk and equal chunks have no imbalance
+    assert O.imbalance(chunks[:1], tensors) == 0.0
+    assert O.imbalance([[O.Segment(0, 0, 15, 0)], [O.Segment(0, 15, 30, 0)], [O.Segment(0, 30, 45, 0)]], tensors) == 0.0
+
+
+def test_jitter_never_exceeds_the_appendix_bound_on_planner_output():
+    """max_k M_k - min_k M_k <= 2 eps_B for M_k = 2M + B(C_k), so the jitter of a plan stays
+    below 2 eps_B / (2M + mean B) (last equation of the appendix); equality when the largest
+    and the smallest chunk lie equally far from the mean."""
+    rng = np.random.default_rng(23)
+    for _ in range(200):
+        n = int(rng.integers(1, 6))
+        tensors = [(int(rng.integers(1, 30)), int(rng.integers(1, 9)), int(rng.integers(0, 2))) for _ in range(n)]
+        budget = int(rng.integers(20, 600))
+        for balanced in (False, True):
+            chunks = O.plan_cycle(tensors, budget, training_cost=True, balanced=balanced)
+            resident = sum(r * c * (4 if d == O.F32 else 2) for r, c, d in tensors)
+            j = O.jitter(O.step_memory(chunks, tensors, resident, True))
+            bound = O.jitter_bound(chunks, tensors, resident, True)
+            assert j <= bound * (1 + 1e-12)
+            costs = [O.chunk_cost_bytes(c, tensors, True) for c in chunks]
+            mean = sum(costs) / len(costs)
+            if abs((max(costs) - mean) - (mean - min(costs))) < 1e-9:
+                assert abs(j - bound) <= 1e-12 * max(bound, 1.0)
+    # two chunks always lie equally far from their mean: the bound is attained
+    tensors = [(7, 9, O.BF16)]
+    chunks = O.plan_cycle(tensors, 2 * 40)
+    assert len(chunks) == 2
+    assert O.jitter(O.step_memory(chunks, tensors, 126, False)) == O.jitter_bound(chunks, tensors, 126, False)
+
+
+def test_plan_balanced_random_invariants():
+    """The balanced plan, alone and with each other option: an exact partition, no chunk above
+    the caller's budget (Section 3 "Method": a predefined byte budget), no more chunks than the
+    greedy plan (exactly as many when tensors are cut anywhere), never a larger imbalance than greedy's capacity search started from, and for one
+    dtype without row groups an imbalance below one element's cost plus the rounding of the
+    capacity to 4 bytes."""
+    rng = np.random.default_rng(29)
+    tried = 0
+    for _ in range(400):
+        n = int(rng.integers(1, 6))
+        uniform = bool(rng.integers(0, 2))
+        d0 = int(rng.integers(0, 2))
+        tensors = [(int(rng.integers(0, 40)), int(rng.integers(0, 7)), d0 if uniform else int(rng.integers(0, 2)))
+                   for _ in range(n)]
+        for tc, rows8 in itertools.product((False, True), (False, True)):
+            budget = int(rng.integers(20 if tc else 4, 500))
+            greedy = O.plan_cycle(tensors, budget, training_cost=tc, rows8=rows8)
+            bal = O.plan_cycle(tensors, budget, training_cost=tc, rows8=rows8, balanced=True)
+            _check_partition(tensors, bal)
+            # the chunk count of a plan cut anywhere never rises with the budget, so the smallest capacity
+            # that needs no more than K chunks needs exactly K; with cuts between row groups a capacity
+            # too small for a group falls back to cuts anywhere and can need fewer
+            assert len(bal) == len(greedy) if not rows8 else len(bal) <= len(greedy)
+            costs = [O.chunk_cost_bytes(c, tensors, tc) for c in bal]
+            assert all(0 < c <= budget for c in costs)
+            if len(bal) < 2:
+                assert bal == greedy
+                continue
+            tried += 1
+            # the capacity actually used is the largest chunk: it is the smallest one (in steps of
+            # 4 bytes from ceil(total / K)) that still gives K chunks, so one step less must not
+            cap = max(costs)
+            total = sum(costs)
+            lowest = max(-(-(-(-total // len(bal))) // 4) * 4, max((4 if d == O.F32 else 2) + (16 if tc else 0)
+                                                                   for r, c, d in tensors if r * c))
+            assert cap <= budget
+            if bal != greedy:
+                # found below the caller's budget: some candidate b in [lowest, budget) gave K chunks and
+                # every earlier candidate gave more
+                b = lowest
+                while len(O._greedy([r * c for r, c, _ in tensors],
+                                    [(4 if d == O.F32 else 2) + (16 if tc else 0) for _, _, d in tensors], b,
+                                    [8 * c for _, c, _ in tensors] if rows8 else None)) > len(greedy):
+                    b += 4
+                assert cap <= b < budget
+                assert len(bal) == len(O.plan_cycle(tensors, b, training_cost=tc, rows8=rows8))
+            if uniform and not rows8:
+                s = (4 if d0 == O.F32 else 2) + (16 if tc else 0)
+                # every chunk but the last is full to within one element; the last holds the rest
+                assert max(costs[:-1]) - min(costs[:-1]) == 0
+                assert cap - costs[-1] < len(bal) * (s + 4)
+                assert O.imbalance(bal, tensors, tc) <= O.imbalance(greedy, tensors, tc) + 1e-9
+    assert tried > 300
+
+
 def test_plan_balanced():
     tensors = [(100, 64, O.BF16), (30, 64, O.BF16), (1, 64, O.BF16), (64, 200, O.BF16)]
     total = sum(r * c for r, c, _ in tensors) * 2
