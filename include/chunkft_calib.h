@@ -10,11 +10,16 @@
 #ifndef CHUNKFT_CALIB_H
 #define CHUNKFT_CALIB_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
 extern "C" {
 #endif
+
+/* Device scratch the two calls need: at least this many bytes, 16-byte aligned, owned by
+ * the caller like every other buffer of the library (which allocates no device memory). */
+#define CHUNKFT_CALIB_SCRATCH_BYTES 4096
 
 /* Runs, on the current device, a kernel that issues nothing but 32x32x16 bf16
  * MFMAs from registers (two waves per SIMD on every compute unit, eight
@@ -25,13 +30,17 @@ extern "C" {
  *                       one, and every MFMA gets other registers than the one
  *                       before it (the situation of a real contraction).
  *   steps            MFMA steps of 8 instructions per wave; a multiple of 4, >= 4.
+ *   scratch          (device) CHUNKFT_CALIB_SCRATCH_BYTES or more; contents are ignored
+ *                    on entry and unspecified on return.
  *   tflops           out (host): sustained rate, 2*32*32*16 flop per MFMA.
  *   shader_mhz       out (host): clock during the kernel (shader cycle counter
  *                    against the constant 100 MHz counter).
- * Blocks until the measurement is done.  Uses one small device allocation that
- * is freed before return.  Returns CHUNKFT_OK or a negative chunkft_status. */
-int chunkft_calib_mfma_bf16(int32_t random_operands, int32_t steps, double* tflops, double* shader_mhz,
-                            void* stream);
+ * Blocks until the measurement is done (it creates two HIP events for the timing and
+ * destroys them before return; no memory is allocated).  Returns CHUNKFT_OK or a
+ * negative status: CHUNKFT_ERR_WORKSPACE for a missing, short or misaligned
+ * scratch. */
+int chunkft_calib_mfma_bf16(int32_t random_operands, int32_t steps, void* scratch, size_t scratch_bytes,
+                            double* tflops, double* shader_mhz, void* stream);
 
 /* The same measurement for either bf16 MFMA shape.
  *   shape  32: 32x32x16 (what the call above runs, and what the weight-gradient kernel
@@ -39,8 +48,8 @@ int chunkft_calib_mfma_bf16(int32_t random_operands, int32_t steps, double* tflo
  *              same flop count per step.  Anything else: CHUNKFT_ERR_INVALID_ARG.
  * The two shapes do the same work per cycle but do not draw the same power, so under
  * the clock limit their sustained rates differ. */
-int chunkft_calib_mfma_bf16_shape(int32_t shape, int32_t random_operands, int32_t steps, double* tflops,
-                                  double* shader_mhz, void* stream);
+int chunkft_calib_mfma_bf16_shape(int32_t shape, int32_t random_operands, int32_t steps, void* scratch,
+                                  size_t scratch_bytes, double* tflops, double* shader_mhz, void* stream);
 
 #ifdef __cplusplus
 }

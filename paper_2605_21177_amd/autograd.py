@@ -1,4 +1,5 @@
-"""Chunk-aware linear operator for torch autograd (Section 3.2; Algorithm 1 line 8).
+"""Chunk-aware linear operator for torch autograd (Section 3.1, gradient of the active
+slices only; Algorithm 1 line 18, the chunk-aware backward).
 
 `chunk_linear(x, W, seg)` is `x @ W^T` whose backward passes the input gradient
 on as usual but never forms the dense weight gradient: it hands the layer's
@@ -25,7 +26,9 @@ class ChunkSegment:
     (`end - begin` elements) on the first micro-batch after `reset()` and adds to
     it on the following ones.
     Fused mode (`master`, `m`, `v`, `hp` given): backward updates the chunk state
-    and the segment of `W` in place; one micro-batch per step.
+    and the segment of `W` in place (a bf16 `W` receives the rounded master, an fp32
+    `W` a copy of it; `master` may also be the segment of an fp32 `W` itself, the
+    parameter then being its own master); one micro-batch per step.
     A segment with `begin == end` (tensor not in the active chunk) makes backward
     skip the weight gradient altogether.
     """
@@ -88,8 +91,8 @@ class _ChunkLinear(torch.autograd.Function):
             if seg.fused:
                 if seg.micro_batches:
                     raise RuntimeError("fused mode takes one micro-batch per optimizer step")
-                Wd = W if W.dtype == torch.bfloat16 else None
-                B.chunkft_wgrad_adamw_fused(layer, seg.begin, seg.end, Wd, seg.master, seg.m, seg.v, seg.hp, ws=ws)
+                # W is what the next forward multiplies with: it always receives the update
+                B.chunkft_wgrad_adamw_fused(layer, seg.begin, seg.end, W, seg.master, seg.m, seg.v, seg.hp, ws=ws)
             else:
                 B.chunkft_chunk_wgrad(layer, seg.begin, seg.end, seg.g, accumulate=seg.micro_batches > 0, ws=ws)
             seg.micro_batches += 1

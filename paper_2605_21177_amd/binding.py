@@ -133,11 +133,11 @@ def lib() -> C.CDLL:
         L.chunkft_schedule_at.restype = C.c_int
         L.chunkft_schedule_at.argtypes = [C.c_int64, C.c_int32, C.c_int64, C.POINTER(ScheduleEntry)]
         L.chunkft_calib_mfma_bf16_shape.restype = C.c_int
-        L.chunkft_calib_mfma_bf16_shape.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double),
-                                                    C.POINTER(C.c_double), C.c_void_p]
+        L.chunkft_calib_mfma_bf16_shape.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t,
+                                                    C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]
         L.chunkft_calib_mfma_bf16.restype = C.c_int
-        L.chunkft_calib_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double),
-                                              C.c_void_p]
+        L.chunkft_calib_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.POINTER(C.c_double),
+                                              C.POINTER(C.c_double), C.c_void_p]
         _lib = L
     return _lib
 
@@ -315,11 +315,20 @@ def chunkft_wgrad_adamw_fused(layer: Layer, begin: int, end: int, W, master, m, 
     return st
 
 
+CALIB_SCRATCH_BYTES = 4096
+
+
+def _calib_scratch():
+    import torch
+    return torch.empty(CALIB_SCRATCH_BYTES, dtype=torch.uint8, device="cuda")
+
+
 def chunkft_calib_mfma_bf16(random_operands: bool, steps: int = 4000, stream=None) -> Tuple[float, float]:
     """(TFLOP/s, shader MHz) that 32x32x16 MFMAs issued from registers sustain on the current device."""
     tf, mhz = C.c_double(0.0), C.c_double(0.0)
-    st = lib().chunkft_calib_mfma_bf16(1 if random_operands else 0, steps, C.byref(tf), C.byref(mhz),
-                                       _stream_ptr(stream))
+    scratch = _calib_scratch()
+    st = lib().chunkft_calib_mfma_bf16(1 if random_operands else 0, steps, scratch.data_ptr(), CALIB_SCRATCH_BYTES,
+                                       C.byref(tf), C.byref(mhz), _stream_ptr(stream))
     if st != OK:
         raise ChunkFTError(st, "chunkft_calib_mfma_bf16")
     return tf.value, mhz.value
@@ -329,8 +338,9 @@ def chunkft_calib_mfma_bf16_shape(shape: int, random_operands: bool, steps: int 
                                   stream=None) -> Tuple[float, float]:
     """The same for MFMA shape 32 (32x32x16) or 16 (16x16x32)."""
     tf, mhz = C.c_double(0.0), C.c_double(0.0)
-    st = lib().chunkft_calib_mfma_bf16_shape(shape, 1 if random_operands else 0, steps, C.byref(tf), C.byref(mhz),
-                                             _stream_ptr(stream))
+    scratch = _calib_scratch()
+    st = lib().chunkft_calib_mfma_bf16_shape(shape, 1 if random_operands else 0, steps, scratch.data_ptr(),
+                                             CALIB_SCRATCH_BYTES, C.byref(tf), C.byref(mhz), _stream_ptr(stream))
     if st != OK:
         raise ChunkFTError(st, "chunkft_calib_mfma_bf16_shape")
     return tf.value, mhz.value

@@ -61,7 +61,8 @@ Checked check_layer(const chunkft_layer* L, int64_t begin, int64_t end) {
   p.begin = begin;
   p.end = end;
   c.mfma = L->kind == CHUNKFT_LINEAR && L->dtype == CHUNKFT_BF16 && mfma_path_ok(p);
-  const Split sp = pick_split(L->kind, L->dtype, L->out, L->in, L->T, begin, end, L->split_k, c.mfma);
+  const Split sp = pick_split(L->kind, L->dtype, L->out, L->in, L->T, begin, end, L->split_k, c.mfma,
+                              device_compute_units());
   p.S = sp.S;
   p.kslab = sp.kslab;
   if (p.S > 1 && (end - begin) > kMaxI64 / 4 / p.S - 64) { c.status = CHUNKFT_ERR_OVERFLOW; return c; }

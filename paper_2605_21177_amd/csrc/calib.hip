@@ -1,6 +1,7 @@
 // Sustained MFMA rate of the device: the measurement aid declared in chunkft_calib.h.
 #include <hip/hip_runtime.h>
 
+#include <cstdint>
 #include <type_traits>
 
 #include "chunkft.h"
@@ -65,23 +66,23 @@ __global__ __launch_bounds__(256, 2) void mfma_rate_kernel(float* sink, int step
 
 }  // namespace
 
-extern "C" int chunkft_calib_mfma_bf16(int32_t random_operands, int32_t steps, double* tflops, double* shader_mhz,
-                                       void* stream) {
-  return chunkft_calib_mfma_bf16_shape(32, random_operands, steps, tflops, shader_mhz, stream);
+extern "C" int chunkft_calib_mfma_bf16(int32_t random_operands, int32_t steps, void* scratch, size_t scratch_bytes,
+                                       double* tflops, double* shader_mhz, void* stream) {
+  return chunkft_calib_mfma_bf16_shape(32, random_operands, steps, scratch, scratch_bytes, tflops, shader_mhz, stream);
 }
 
-extern "C" int chunkft_calib_mfma_bf16_shape(int32_t shape, int32_t random_operands, int32_t steps, double* tflops,
-                                             double* shader_mhz, void* stream) {
+extern "C" int chunkft_calib_mfma_bf16_shape(int32_t shape, int32_t random_operands, int32_t steps, void* scratch,
+                                             size_t scratch_bytes, double* tflops, double* shader_mhz, void* stream) {
   if (!tflops || !shader_mhz || steps < 4 || steps % 4 != 0 || steps > (1 << 20)) return CHUNKFT_ERR_INVALID_ARG;
   if (shape != 32 && shape != 16) return CHUNKFT_ERR_INVALID_ARG;
+  if (!scratch || scratch_bytes < CHUNKFT_CALIB_SCRATCH_BYTES || (reinterpret_cast<uintptr_t>(scratch) & 15u))
+    return CHUNKFT_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   int dev = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess) return CHUNKFT_ERR_HIP;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return CHUNKFT_ERR_HIP;
-  void* buf = nullptr;
-  if (hipMalloc(&buf, 4096) != hipSuccess) return CHUNKFT_ERR_HIP;
-  float* sink = (float*)buf;
-  unsigned long long* clk = (unsigned long long*)((char*)buf + 2048);
+  float* sink = (float*)scratch;
+  unsigned long long* clk = (unsigned long long*)((char*)scratch + 2048);
   hipEvent_t e0 = nullptr, e1 = nullptr;
   int rc = CHUNKFT_ERR_HIP;
   const int grid = 2 * cus, reps = 5;
@@ -108,6 +109,5 @@ extern "C" int chunkft_calib_mfma_bf16_shape(int32_t shape, int32_t random_opera
   } while (false);
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);
-  (void)hipFree(buf);
   return rc;
 }

@@ -56,9 +56,26 @@ struct Split {
   int64_t kslab;
 };
 
+// Row decomposition of a chunk [begin, end) of W [out, in] for the MFMA kernel.
+struct RowSplit {
+  int64_t rb0, rb1;     // MFMA body rows [rb0, rb1), empty if rb1 <= rb0
+  int64_t lead_base;    // 8-aligned group holding the leading edge rows, or -1
+  int64_t trail_row;    // partial last row outside the body, or -1
+};
+RowSplit split_rows(const WgradProblem& p);               // needs p.begin, p.end, p.in only
+
+// Tile of the plain MFMA gradient and of the FMA kernel: what the token split is chosen from.
+constexpr int64_t kMainTileM = 256, kMainTileN = 256, kMainTileK = 32;
+constexpr int64_t kSimtTileM = 64, kSimtTileN = 64, kSimtTileK = 16;
+
+constexpr int kMaxDevices = 64;
+constexpr int kDefaultComputeUnits = 256;                 // MI355X
+int device_compute_units();                               // of the current device (kernels.hip)
+
+// shape.cpp: pure functions of the shapes (and of the compute-unit count they are given)
 bool mfma_path_ok(const WgradProblem& p);                 // alignment / shape rules of the MFMA kernel
 Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T, int64_t begin,
-                 int64_t end, int32_t forced, bool mfma);
+                 int64_t end, int32_t forced, bool mfma, int compute_units);
 
 // All launchers return a hipError_t as int (0 = success).
 int launch_wgrad_bf16_mfma(const WgradProblem& p, int mode, const Sinks& s, void* stream);

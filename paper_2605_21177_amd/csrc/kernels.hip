@@ -20,6 +20,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 
 #include "internal.h"
@@ -1294,8 +1295,6 @@ __global__ __launch_bounds__(256) void elementwise_kernel(const ElemParams q) {
 // ---------------------------------------------------------------------------
 namespace {
 
-constexpr int kNumCU = 256;
-
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Start delay (units of 8128 cycles) of the second workgroup of each compute unit in the fused
@@ -1307,44 +1306,19 @@ using MainCfg = RingCfg<2, 4>;    // 256 x 256 tiles, four slabs of 33 KB in LDS
 using FusedCfg = RingCfg<1, 3>;   // 128 x 256 tiles, three slabs of 25 KB, two workgroups per compute unit
                                   // (the fused call, and plain gradients with few tiles)
 
-struct RowSplit {
-  int64_t rb0, rb1;     // MFMA body rows [rb0, rb1), empty if rb1 <= rb0
-  int64_t lead_base;    // 8-aligned group holding the leading edge rows, or -1
-  int64_t trail_row;    // partial last row outside the body, or -1
-};
-
-// Body = complete rows from the first multiple of 8 on.  Everything before it
-// lies in the one 8-row group [rb0 - 8, rb0) (at most the partial first row and
-// 7 complete rows); after it there is at most the partial last row.
-RowSplit split_rows(const WgradProblem& p) {
-  RowSplit rs{};
-  const int64_t r0 = p.begin / p.in, c0 = p.begin % p.in;
-  const int64_t r1 = (p.end - 1) / p.in, c1 = (p.end - 1) % p.in + 1;
-  const int64_t full0 = r0 + (c0 != 0 ? 1 : 0);           // first complete row
-  const int64_t full1 = r1 + 1 - (c1 != p.in ? 1 : 0);    // one past the last complete row
-  const int64_t rb0 = (full0 + 7) / 8 * 8;
-  const bool body = full1 > rb0;
-  rs.rb0 = rb0;
-  rs.rb1 = body ? full1 : rb0;
-  rs.lead_base = r0 < rb0 ? rb0 - 8 : -1;
-  const int64_t first_after = body ? full1 : rb0;          // rows from here on are not in the lead group
-  rs.trail_row = r1 >= first_after ? r1 : -1;
-  return rs;
-}
-
 template <class C, int MODE>
 int launch_mfma_mode(const MfmaParams& q, int grid, hipStream_t st) {
   // The dynamic LDS limit is a per-device attribute of the kernel; raising it is idempotent, so
   // a race between threads only repeats the call.
-  static bool attr_set[64] = {};
+  static std::atomic<bool> attr_set[kMaxDevices] = {};
   const auto kern = &wgrad_mfma_kernel<C, MODE>;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return (int)hipErrorInvalidDevice;
-  if (dev < 0 || dev >= 64 || !attr_set[dev]) {
+  if (dev < 0 || dev >= kMaxDevices || !attr_set[dev].load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)C::LDS_BYTES);
     if (e != hipSuccess) return (int)e;
-    if (dev >= 0 && dev < 64) attr_set[dev] = true;
+    if (dev >= 0 && dev < kMaxDevices) attr_set[dev].store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS_BYTES, st, q);
   return (int)hipGetLastError();
@@ -1352,52 +1326,27 @@ int launch_mfma_mode(const MfmaParams& q, int grid, hipStream_t st) {
 
 }  // namespace
 
-bool mfma_path_ok(const WgradProblem& p) {
-  const auto a16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
-  if (!(p.in % 8 == 0 && p.out % 8 == 0 && p.ldx % 8 == 0 && p.lddy % 8 == 0 && a16(p.X) && a16(p.dY)))
-    return false;
-  if (p.in >= (1 << 21)) return false;      // the epilogue's 32-bit tile offsets
-  // the 32-bit byte offsets of the global->LDS loads: a row / column index plus up to 63 tokens
-  if (p.out + 64 * p.lddy >= (int64_t(1) << 31) || p.in + 64 * p.ldx >= (int64_t(1) << 31)) return false;
-  return true;
-}
+static_assert(MainCfg::BM == kMainTileM && MainCfg::BN == kMainTileN && MainCfg::BK == kMainTileK,
+              "the token split is chosen from these tile sizes");
 
-Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T, int64_t begin,
-                 int64_t end, int32_t forced, bool mfma) {
-  (void)out; (void)dtype;
-  if (kind != 0) return {1, T};                       // scale vectors are never split
-  const int64_t bm = mfma ? MainCfg::BM : 64, bn = mfma ? MainCfg::BN : 64;
-  const int64_t bk = mfma ? MainCfg::BK : 16;
-  int64_t S = forced;
-  if (S <= 0) {
-    int64_t rows = (end - 1) / in - begin / in + 1;
-    if (mfma) {                                       // the MFMA kernel tiles the body rows only
-      WgradProblem tmp{};
-      tmp.begin = begin;
-      tmp.end = end;
-      tmp.in = in;
-      const RowSplit rs = split_rows(tmp);
-      rows = rs.rb1 > rs.rb0 ? rs.rb1 - rs.rb0 : 1;
-    }
-    const int64_t tiles = ceil_div(rows, bm) * ceil_div(in, bn);
-    S = 1;
-    const int64_t slots = kNumCU;                     // resident workgroups
-    if (mfma && tiles <= slots / 4) {
-      // Splitting pays only when the 256 x 256 tiles fill at most a quarter of the compute units.
-      // A slab costs its tokens' share of the loop, every further slab 8 bytes per element of
-      // partial traffic plus one more set-up and epilogue per tile: time ~ a T / S + b S tiles,
-      // least at S = sqrt(a T / (b tiles)).  a / b = 1 / 12 fits the measured grid (16 - 192
-      // tiles x 1024 - 8192 tokens x 1 - 16 slabs, plain and fused call, in = 4096); more than 8
-      // slabs never won, and from 128 tiles on one slab is best.
-      S = 1;
-      while ((S + 1) * (S + 1) * 12 * tiles <= T && S < 8) ++S;
-      if (S > slots / tiles) S = slots / tiles;
-      if (S > T / 256) S = T / 256 > 0 ? T / 256 : 1;    // never slabs of fewer than 256 tokens
-    }
+// Compute units of the current device, asked once per device (a launch-shape input: how many
+// workgroups fill the part).  Without a device -- the host-only size queries on a machine
+// that has none -- the count of the MI355X this library is written for.
+int device_compute_units() {
+  static std::atomic<int> cached[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0) { (void)hipGetLastError(); return kDefaultComputeUnits; }
+  if (dev < kMaxDevices) {
+    const int c = cached[dev].load(std::memory_order_relaxed);
+    if (c > 0) return c;
   }
-  int64_t kslab = ceil_div(ceil_div(T, S), bk) * bk;
-  S = ceil_div(T, kslab);                             // no empty slab
-  return {(int32_t)S, kslab};
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+    (void)hipGetLastError();
+    return kDefaultComputeUnits;
+  }
+  if (dev < kMaxDevices) cached[dev].store(cus, std::memory_order_relaxed);
+  return cus;
 }
 
 template <class C>
@@ -1462,7 +1411,7 @@ int launch_wgrad_bf16_mfma(const WgradProblem& p, int mode, const Sinks& s, void
   // tile too: twice the workgroups, each element still summed over the tokens in the same order.
   const RowSplit rs = split_rows(p);
   const int64_t big_tiles = ceil_div(rs.rb1 - rs.rb0, MainCfg::BM) * ceil_div(p.in, MainCfg::BN) * p.S;
-  if (big_tiles <= kNumCU / 2) return launch_mfma_cfg<FusedCfg>(p, mode, s, (hipStream_t)stream);
+  if (big_tiles <= device_compute_units() / 2) return launch_mfma_cfg<FusedCfg>(p, mode, s, (hipStream_t)stream);
   return launch_mfma_cfg<MainCfg>(p, mode, s, (hipStream_t)stream);
 }
 
@@ -1568,7 +1517,7 @@ static int launch_elem(ElemParams& q, int mode, hipStream_t st) {
   // One block of 256 threads per CU, one group of four elements per thread in flight: the
   // seven streams of the update then reach 5.9 - 6.0 TB/s; with twice the blocks, or twice the
   // groups per trip, HBM efficiency drops to 5.3 - 5.4 TB/s (measured sweep).
-  const int64_t cap = (int64_t)kNumCU;
+  const int64_t cap = (int64_t)device_compute_units();
   if (blocks > cap) blocks = cap;
   if (blocks < 1) blocks = 1;
   switch (mode) {

@@ -1,0 +1,82 @@
+// Host-side shape logic of the weight-gradient calls: which rows the MFMA kernel tiles, whether
+// a call can take the MFMA path, and into how many token slabs it is split.  Pure functions of
+// their arguments (no HIP), so that they can be built and fuzzed on a machine without a GPU.
+
+#include <cstdint>
+
+#include "internal.h"
+
+namespace chunkft {
+
+namespace {
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+}  // namespace
+
+// Body = complete rows from the first multiple of 8 on.  Everything before it
+// lies in the one 8-row group [rb0 - 8, rb0) (at most the partial first row and
+// 7 complete rows); after it there is at most the partial last row.
+RowSplit split_rows(const WgradProblem& p) {
+  RowSplit rs{};
+  const int64_t r0 = p.begin / p.in, c0 = p.begin % p.in;
+  const int64_t r1 = (p.end - 1) / p.in, c1 = (p.end - 1) % p.in + 1;
+  const int64_t full0 = r0 + (c0 != 0 ? 1 : 0);           // first complete row
+  const int64_t full1 = r1 + 1 - (c1 != p.in ? 1 : 0);    // one past the last complete row
+  const int64_t rb0 = (full0 + 7) / 8 * 8;
+  const bool body = full1 > rb0;
+  rs.rb0 = rb0;
+  rs.rb1 = body ? full1 : rb0;
+  rs.lead_base = r0 < rb0 ? rb0 - 8 : -1;
+  const int64_t first_after = body ? full1 : rb0;          // rows from here on are not in the lead group
+  rs.trail_row = r1 >= first_after ? r1 : -1;
+  return rs;
+}
+
+bool mfma_path_ok(const WgradProblem& p) {
+  const auto a16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+  if (!(p.in % 8 == 0 && p.out % 8 == 0 && p.ldx % 8 == 0 && p.lddy % 8 == 0 && a16(p.X) && a16(p.dY)))
+    return false;
+  if (p.in >= (1 << 21)) return false;      // the epilogue's 32-bit tile offsets
+  // the 32-bit byte offsets of the global->LDS loads: a row / column index plus up to 63 tokens
+  if (p.out + 64 * p.lddy >= (int64_t(1) << 31) || p.in + 64 * p.ldx >= (int64_t(1) << 31)) return false;
+  return true;
+}
+
+Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T, int64_t begin,
+                 int64_t end, int32_t forced, bool mfma, int compute_units) {
+  (void)out; (void)dtype;
+  if (kind != 0) return {1, T};                       // only linear layers are ever split
+  const int64_t bm = mfma ? kMainTileM : kSimtTileM, bn = mfma ? kMainTileN : kSimtTileN;
+  const int64_t bk = mfma ? kMainTileK : kSimtTileK;
+  int64_t S = forced;
+  if (S <= 0) {
+    int64_t rows = (end - 1) / in - begin / in + 1;
+    if (mfma) {                                       // the MFMA kernel tiles the body rows only
+      WgradProblem tmp{};
+      tmp.begin = begin;
+      tmp.end = end;
+      tmp.in = in;
+      const RowSplit rs = split_rows(tmp);
+      rows = rs.rb1 > rs.rb0 ? rs.rb1 - rs.rb0 : 1;
+    }
+    const int64_t tiles = ceil_div(rows, bm) * ceil_div(in, bn);
+    S = 1;
+    const int64_t slots = compute_units > 0 ? compute_units : kDefaultComputeUnits;   // resident workgroups
+    if (mfma && tiles <= slots / 4) {
+      // Splitting pays only when the 256 x 256 tiles fill at most a quarter of the compute units.
+      // A slab costs its tokens' share of the loop, every further slab 8 bytes per element of
+      // partial traffic plus one more set-up and epilogue per tile: time ~ a T / S + b S tiles,
+      // least at S = sqrt(a T / (b tiles)).  a / b = 1 / 12 fits the measured grid (16 - 192
+      // tiles x 1024 - 8192 tokens x 1 - 16 slabs, plain and fused call, in = 4096); more than 8
+      // slabs never won, and from 128 tiles on one slab is best.
+      S = 1;
+      while ((S + 1) * (S + 1) * 12 * tiles <= T && S < 8) ++S;
+      if (S > slots / tiles) S = slots / tiles;
+      if (S > T / 256) S = T / 256 > 0 ? T / 256 : 1;    // never slabs of fewer than 256 tokens
+    }
+  }
+  int64_t kslab = ceil_div(ceil_div(T, S), bk) * bk;
+  S = ceil_div(T, kslab);                             // no empty slab
+  return {(int32_t)S, kslab};
+}
+
+}  // namespace chunkft

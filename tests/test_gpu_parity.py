@@ -468,8 +468,16 @@ def test_config3_scaled_cycle(budget_mib_x16, rows8):
 def test_rotating_schedule_trajectory():
     """Algorithm 1 end to end on a small block: chunks rotate with interval 2 for two and a half
     cycles, every step has its own output gradients, the active chunk's segments are updated
-    with the chunk's own counter.  Master weights, moments and bf16 copies of every tensor
-    after the last step against the same schedule run on the oracle."""
+    with the chunk's own counter.  Checked step by step with the single-step rules, so that no
+    tolerance has to grow with the number of steps:
+      * the gradient of every segment (the un-fused call on the same operands, whose bits the
+        fused call's internal gradient equals) against the oracle's, relative Frobenius 3e-3;
+      * the state after the fused call against the oracle's AdamW applied to the GPU's own
+        gradient and the GPU's own state before the step, element-wise 1e-5;
+      * the bf16 copy bit-exact against the rounded GPU master;
+    and at the end the whole trajectory: the oracle's schedule, counters and AdamW run from the
+    initial state on the GPU's gradients must land on the GPU's final state, element-wise 1e-5
+    (per-step differences are fp32 rounding, about 1e-7, and do not pass through a sign)."""
     layers = WL.config3(scale=16, T=64)
     tensors = [(c.out, c.n_in, c.dtype, c.kind) for c in layers]
     budget = sum(c.numel for c in layers) * 2 // 3 + 2              # three chunks, mid-row cuts
@@ -491,9 +499,11 @@ def test_rotating_schedule_trajectory():
     params = [WL.as_f64(c.W0).reshape(-1).copy() for c in layers]
     ostate = [dict(m=np.zeros(ch[2]), v=np.zeros(ch[2])) for ch in chunks]
     sched = O.rotating_schedule(n_steps, K, interval)
+    visits = [0] * K
     for t in range(n_steps):
         k, load, off, n = B.chunkft_schedule_at(t, K, interval)
         assert (k, load, off, n) == sched[t]
+        visits[k] += 1
         s0, s1, numel, _ = chunks[k]
         master, m, v = state[k]
         for (ti, b, e, o) in segs[s0:s1]:
@@ -502,31 +512,45 @@ def test_rotating_schedule_trajectory():
             layer = B.make_layer(case.kind, dls[ti].X, dY_t.to(H.DEV), case.out, case.n_in)
             ws = H.workspace_for(layer, b, e)
             cnt = e - b
+            before = tuple(x[o:o + cnt].cpu().numpy().astype(np.float64) for x in (master, m, v))
+            g_gpu = torch.empty(cnt, dtype=torch.float32, device=H.DEV)
+            B.chunkft_chunk_wgrad(layer, b, e, g_gpu, ws=ws)
             B.chunkft_wgrad_adamw_fused(layer, b, e, Wd[ti], master[o:o + cnt], m[o:o + cnt], v[o:o + cnt],
                                         B.hparams(step=n, **HP), ws=ws)
             torch.cuda.synchronize()
+            assert H.workspace_intact(ws)
+            g64 = g_gpu.cpu().numpy().astype(np.float64)
             X64, dY64 = WL.as_f64(case.X), WL.as_f64(dY_t)
-            g = (O.chunk_wgrad(X64, dY64, b, e, dense=False) if case.kind == WL.LINEAR
-                 else O.vector_wgrad(X64, dY64, b, e))
-            th, mm, vv = O.adamw_step(g, params[ti][b:e], ostate[k]["m"][o:o + cnt], ostate[k]["v"][o:o + cnt],
+            g_ref = (O.chunk_wgrad(X64, dY64, b, e, dense=False) if case.kind == WL.LINEAR
+                     else O.vector_wgrad(X64, dY64, b, e))
+            assert H.rel_frobenius(g64, g_ref) <= 3e-3
+            # this step alone: the oracle's update of the GPU's state by the GPU's gradient
+            ref = O.adamw_step(g64, *before, step=n, **HP)
+            tag = f"step {t} chunk {k} tensor {ti}"
+            H.assert_elementwise(master[o:o + cnt].cpu().numpy(), ref[0], 1e-2, "theta " + tag)
+            H.assert_elementwise(m[o:o + cnt].cpu().numpy(), ref[1], 1e-2, "m " + tag)
+            H.assert_elementwise(v[o:o + cnt].cpu().numpy(), ref[2], 0.0, "v " + tag)
+            bits = WL.bits_u16(Wd[ti][b:e].cpu())
+            assert np.array_equal(bits, O.bf16_bits(master[o:o + cnt].cpu().numpy().astype(np.float64)))
+            # the whole trajectory on the oracle's own state
+            th, mm, vv = O.adamw_step(g64, params[ti][b:e], ostate[k]["m"][o:o + cnt], ostate[k]["v"][o:o + cnt],
                                       step=n, **HP)
             params[ti][b:e] = th
             ostate[k]["m"][o:o + cnt] = mm
             ostate[k]["v"][o:o + cnt] = vv
-    # every chunk was visited at least twice; compare everything
+    assert min(visits) >= 2 * interval                      # every chunk came round at least twice
     for k, (s0, s1, numel, _) in enumerate(chunks):
         master, m, v = (x.cpu().numpy() for x in state[k])
-        H.assert_scale_relative(m, ostate[k]["m"], f"m of chunk {k}", rtol=2e-5)
-        H.assert_scale_relative(v, ostate[k]["v"], f"v of chunk {k}", rtol=2e-5)
+        H.assert_elementwise(m, ostate[k]["m"], 1e-2, f"m of chunk {k} after {n_steps} steps")
+        H.assert_elementwise(v, ostate[k]["v"], 0.0, f"v of chunk {k} after {n_steps} steps")
         for (ti, b, e, o) in segs[s0:s1]:
-            # the first update of a cold chunk is a sign step where the gradient is tiny (the
-            # conditioning note of the harness); its size is lr, so allow two steps of it per visit
-            d = np.abs(master[o:o + e - b].astype(np.float64) - params[ti][b:e])
-            assert np.quantile(d, 0.999) <= 2e-5 * np.max(np.abs(params[ti][b:e])) and d.max() <= 4 * HP["lr"]
+            H.assert_elementwise(master[o:o + e - b], params[ti][b:e], 1e-2, f"theta of chunk {k} tensor {ti} after {n_steps} steps")
     for ti, case in enumerate(layers):
+        # the oracle's bf16 copy of its own trajectory: the GPU's may differ by one grid step where a
+        # 1e-7 difference of the masters falls on a rounding boundary
         bits = WL.bits_u16(Wd[ti].cpu()).astype(np.int64)
         ref = O.bf16_bits(params[ti]).astype(np.int64)
-        assert np.quantile(np.abs(bits - ref), 0.999) <= 1
+        assert np.abs(bits - ref).max() <= 1
 
 
 def test_calls_replay_from_a_captured_graph():

@@ -379,13 +379,26 @@ def test_calibration_call_validates_before_touching_the_device():
     tf, mhz = C.c_double(0.0), C.c_double(0.0)
     bad = [(1, 0), (1, 6), (1, -4), (0, (1 << 20) + 4)]
     for rnd, steps in bad:
-        assert lib.chunkft_calib_mfma_bf16(rnd, steps, C.byref(tf), C.byref(mhz), None) == B.ERR_INVALID_ARG
-    assert lib.chunkft_calib_mfma_bf16(1, 8, None, C.byref(mhz), None) == B.ERR_INVALID_ARG
+        assert lib.chunkft_calib_mfma_bf16(rnd, steps, P, 4096, C.byref(tf), C.byref(mhz), None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_calib_mfma_bf16(1, 8, P, 4096, None, C.byref(mhz), None) == B.ERR_INVALID_ARG
     for shape in (0, 8, 64, -16):        # only the two bf16 MFMA shapes exist
-        assert lib.chunkft_calib_mfma_bf16_shape(shape, 1, 8, C.byref(tf), C.byref(mhz), None) == B.ERR_INVALID_ARG
+        assert lib.chunkft_calib_mfma_bf16_shape(shape, 1, 8, P, 4096, C.byref(tf), C.byref(mhz), None) == B.ERR_INVALID_ARG
     for shape in (16, 32):
-        assert lib.chunkft_calib_mfma_bf16_shape(shape, 1, 6, C.byref(tf), C.byref(mhz), None) == B.ERR_INVALID_ARG
-        assert lib.chunkft_calib_mfma_bf16_shape(shape, 1, 8, C.byref(tf), None, None) == B.ERR_INVALID_ARG
+        assert lib.chunkft_calib_mfma_bf16_shape(shape, 1, 6, P, 4096, C.byref(tf), C.byref(mhz), None) == B.ERR_INVALID_ARG
+        assert lib.chunkft_calib_mfma_bf16_shape(shape, 1, 8, P, 4096, C.byref(tf), None, None) == B.ERR_INVALID_ARG
+        # the scratch is the caller's: missing, short or misaligned is refused (nothing is allocated here)
+        assert lib.chunkft_calib_mfma_bf16_shape(shape, 1, 8, None, 4096, C.byref(tf), C.byref(mhz), None) == B.ERR_WORKSPACE
+        assert lib.chunkft_calib_mfma_bf16_shape(shape, 1, 8, P, 4095, C.byref(tf), C.byref(mhz), None) == B.ERR_WORKSPACE
+        assert lib.chunkft_calib_mfma_bf16_shape(shape, 1, 8, P + 8, 4096, C.byref(tf), C.byref(mhz), None) == B.ERR_WORKSPACE
+
+
+def test_no_source_of_the_library_allocates_device_memory():
+    """Ownership rule of include/chunkft.h: every device buffer is the caller's."""
+    csrc = os.path.join(ROOT, "paper_2605_21177_amd", "csrc")
+    for f in os.listdir(csrc):
+        text = open(os.path.join(csrc, f)).read()
+        for call in ("hipMalloc", "hipFree", "hipMallocAsync", "hipExtMallocWithFlags", "hipHostMalloc", "hipMallocManaged"):
+            assert call + "(" not in text, (f, call)
 
 
 def test_schedule_matches_the_simulated_algorithm():
@@ -426,3 +439,25 @@ def test_plan_counts_astronomic_chunk_numbers_at_once():
     # the first tensor ends a chunk exactly (2^60 is not a multiple of 50: 2^60 % 50 = 26 elements in
     # its last chunk, which the 21 elements of the second tensor join)
     assert ns.value == -(-(1 << 60) // 50) + 1
+
+
+def test_host_code_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """plan.cpp, api.cpp and shape.cpp built for the CPU with -fsanitize=address,undefined and driven
+    by tests/host_sanitize.cpp: random plans (count-then-fill, coverage, budgets near int64), plan
+    summaries, schedules, and a few hundred thousand device-call argument sets whose launches are
+    replaced by host-side checks of what the kernels would have been given."""
+    import shutil
+    import subprocess
+    gxx = shutil.which("g++")
+    assert gxx, "g++ is part of the image"
+    csrc = os.path.join(ROOT, "paper_2605_21177_amd", "csrc")
+    exe = str(tmp_path / "host_sanitize")
+    cmd = [gxx, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-static-libasan", "-I", os.path.join(ROOT, "include"), "-I", csrc,
+           os.path.join(ROOT, "tests", "host_sanitize.cpp")]
+    cmd += [os.path.join(csrc, f) for f in ("plan.cpp", "api.cpp", "shape.cpp")] + ["-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stderr[-2000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300, env=env)
+    assert r.returncode == 0 and r.stdout.startswith("ok:"), (r.stdout[-1000:], r.stderr[-3000:])
