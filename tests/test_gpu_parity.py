@@ -509,7 +509,8 @@ def test_rotating_schedule_trajectory():
         for (ti, b, e, o) in segs[s0:s1]:
             case = layers[ti]
             dY_t = (case.dY.float() * float(scales[t])).to(case.dY.dtype)
-            layer = B.make_layer(case.kind, dls[ti].X, dY_t.to(H.DEV), case.out, case.n_in)
+            dY_dev = dY_t.to(H.DEV)              # the layer descriptor holds its address only: keep it alive
+            layer = B.make_layer(case.kind, dls[ti].X, dY_dev, case.out, case.n_in)
             ws = H.workspace_for(layer, b, e)
             cnt = e - b
             before = tuple(x[o:o + cnt].cpu().numpy().astype(np.float64) for x in (master, m, v))
