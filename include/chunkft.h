@@ -54,7 +54,8 @@ typedef enum {
   CHUNKFT_ERR_WORKSPACE = -4,        /* workspace missing, misaligned or smaller than chunkft_workspace_bytes */
   CHUNKFT_ERR_BUFFER_TOO_SMALL = -5, /* planner output arrays too short; required counts were written */
   CHUNKFT_ERR_HIP = -6,              /* the HIP runtime refused a launch */
-  CHUNKFT_ERR_OVERFLOW = -7          /* an element or byte count does not fit int64 */
+  CHUNKFT_ERR_OVERFLOW = -7,         /* an element or byte count does not fit int64 */
+  CHUNKFT_ERR_STATIC_WORKSPACE = -8  /* the call needs more workspace than CHUNKFT_STATIC_WORKSPACE_BYTES */
 } chunkft_status;
 
 typedef enum { CHUNKFT_F32 = 0, CHUNKFT_BF16 = 1 } chunkft_dtype;
@@ -321,6 +322,30 @@ int chunkft_wgrad_adamw_fused(const chunkft_layer* L, int64_t begin, int64_t end
                               void* W, float* master, float* m, float* v,
                               const chunkft_adamw_hparams* hp,
                               void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * The fused call without a workspace argument
+ *
+ * For callers that cannot allocate device memory or have none to hand over: code
+ * under HIP graph capture, tight serving or training loops, harnesses that forbid
+ * allocation.  The same call as chunkft_wgrad_adamw_fused, bit for bit and with the
+ * same argument rules, but whatever workspace it needs (token-slab partial sums,
+ * per-token statistics of the normalising kinds) lies in a device array of
+ * CHUNKFT_STATIC_WORKSPACE_BYTES that is part of the library: every GPU the library
+ * runs on holds one copy from the first such call on it until the process ends.
+ * A call that would need more returns CHUNKFT_ERR_STATIC_WORKSPACE, nothing enqueued
+ * (chunkft_workspace_bytes tells beforehand).  Neither this call nor anything under
+ * it allocates or frees memory.  The first call on a device asks the runtime for the
+ * array's address (make it outside a graph capture).  All calls on one GPU share the
+ * one array: two that overlap in time (different streams, or graphs replayed side by
+ * side) race on it; calls on one stream are ordered and safe.  Nothing in the array
+ * is read before the same call has written it, so no clearing is needed between calls.
+ * ---------------------------------------------------------------------- */
+#define CHUNKFT_STATIC_WORKSPACE_BYTES (64u << 20)
+
+int chunkft_wgrad_adamw_fused_static(const chunkft_layer* L, int64_t begin, int64_t end,
+                                     void* W, float* master, float* m, float* v,
+                                     const chunkft_adamw_hparams* hp, void* stream);
 
 const char* chunkft_status_string(int status);
 int chunkft_version(void);   /* major * 10000 + minor * 100 + patch */

@@ -23,6 +23,8 @@ ERR_WORKSPACE = -4
 ERR_BUFFER_TOO_SMALL = -5
 ERR_HIP = -6
 ERR_OVERFLOW = -7
+ERR_STATIC_WORKSPACE = -8
+STATIC_WORKSPACE_BYTES = 64 << 20
 
 F32 = 0
 BF16 = 1
@@ -114,6 +116,10 @@ def lib() -> C.CDLL:
                                                 C.c_void_p, C.c_void_p, C.c_void_p,
                                                 C.POINTER(AdamWHparams), C.c_void_p, C.c_size_t,
                                                 C.c_void_p]
+        L.chunkft_wgrad_adamw_fused_static.restype = C.c_int
+        L.chunkft_wgrad_adamw_fused_static.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64, C.c_void_p,
+                                                       C.c_void_p, C.c_void_p, C.c_void_p,
+                                                       C.POINTER(AdamWHparams), C.c_void_p]
         L.chunkft_status_string.restype = C.c_char_p
         L.chunkft_status_string.argtypes = [C.c_int]
         L.chunkft_version.restype = C.c_int
@@ -143,7 +149,8 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ("chunkft_plan_cycle", "chunkft_plan_stats", "chunkft_split_k", "chunkft_workspace_bytes", "chunkft_chunk_wgrad",
-           "chunkft_adamw_chunk", "chunkft_wgrad_adamw_fused", "chunkft_status_string",
+           "chunkft_adamw_chunk", "chunkft_wgrad_adamw_fused", "chunkft_wgrad_adamw_fused_static",
+           "chunkft_status_string",
            "chunkft_version", "chunkft_calib_mfma_bf16", "chunkft_calib_mfma_bf16_shape", "chunkft_schedule_at",
            "chunkft_mover_create", "chunkft_mover_destroy", "chunkft_mover_load", "chunkft_mover_await_load",
            "chunkft_mover_offload", "chunkft_mover_sync")
@@ -321,6 +328,16 @@ CALIB_SCRATCH_BYTES = 4096
 def _calib_scratch():
     import torch
     return torch.empty(CALIB_SCRATCH_BYTES, dtype=torch.uint8, device="cuda")
+
+
+def chunkft_wgrad_adamw_fused_static(layer: Layer, begin: int, end: int, W, master, m, v, hp: AdamWHparams,
+                                     stream=None, check: bool = True) -> int:
+    """The fused call with its workspace in the library's own static device array (no allocation)."""
+    st = lib().chunkft_wgrad_adamw_fused_static(C.byref(layer), begin, end, _ptr(W), _ptr(master), _ptr(m),
+                                                _ptr(v), C.byref(hp), _stream_ptr(stream))
+    if check and st != OK:
+        raise ChunkFTError(st, "chunkft_wgrad_adamw_fused_static")
+    return st
 
 
 def chunkft_calib_mfma_bf16(random_operands: bool, steps: int = 4000, stream=None) -> Tuple[float, float]:

@@ -19,7 +19,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libchunkft.so")
 
-SOURCES = ["kernels.hip", "calib.hip", "api.cpp", "shape.cpp", "plan.cpp", "mover.cpp"]
+SOURCES = ["kernels.hip", "static_ws.hip", "calib.hip", "api.cpp", "shape.cpp", "plan.cpp", "mover.cpp"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

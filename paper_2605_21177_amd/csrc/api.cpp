@@ -222,6 +222,7 @@ extern "C" const char* chunkft_status_string(int status) {
     case CHUNKFT_ERR_BUFFER_TOO_SMALL: return "output arrays too small; required counts returned";
     case CHUNKFT_ERR_HIP: return "HIP runtime error on launch";
     case CHUNKFT_ERR_OVERFLOW: return "size does not fit in int64";
+    case CHUNKFT_ERR_STATIC_WORKSPACE: return "call needs more workspace than the library's static array holds";
     default: return "unknown status";
   }
 }
