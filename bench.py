@@ -58,6 +58,9 @@ def main():
                     help="also run one cycle over a whole Llama-3-8B transformer block (configs[2]: q, k, v, o, "
                          "gate, up, down and two norm vectors, T = 1024) with the planner's chunks for a 256 MiB "
                          "budget: one fused call per segment, timed per chunk; reported under \"block_cycle\"")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the \"per_config\" block (every other configuration of the task's list timed on "
+                         "device-generated operands of its shapes, a few milliseconds each)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region, run a plain device copy of known size (256 MiB read, "
                          "256 MiB written, three times): the calibration point for rocprofv3 --pmc "
@@ -225,6 +228,9 @@ def main():
                            "algorithmic_bytes": adamw_bytes},
     }
 
+    if not args.no_per_config:
+        out["per_config"] = per_config(torch, B, WL, dev, dict(WL.HPARAMS), cfg2=(layer, begin, end, W, g, ws))
+
     if args.sweep:
         out["sweep"] = sweep(torch, B, dev, dict(WL.HPARAMS))
 
@@ -351,10 +357,11 @@ def streamed_state(torch, B, dev, layer, begin, end, W, h_for, ws):
             "note": "bound by the host link: a visit moves %.0f MB, its kernels take %.2f ms" % (per_visit_bytes / 1e6, kernels * 1e3)}
 
 
-def block_cycle(torch, B, dev, hp):
-    """One cycle over the nine tensors of a Llama-3-8B block: plan with a 256 MiB budget, then per
-    chunk one fused call per segment on one stream (a chunk may cross tensors), median of 10.
-    The state of a chunk is kept as one set of arrays per segment, each in the recommended layout."""
+def block_cycle(torch, B, dev, hp, reps=10, graph=True):
+    """One cycle over the nine tensors of a Llama-3-8B block (configs[2]): plan with a 256 MiB budget,
+    then per chunk one fused call per segment on one stream (a chunk may cross tensors), median of
+    `reps`.  The state of a chunk is kept as one set of arrays per segment, each in the recommended
+    layout."""
     T = 1024
     gen = torch.Generator(device=dev)
     gen.manual_seed(211773)
@@ -380,7 +387,6 @@ def block_cycle(torch, B, dev, hp):
     _, chunks, segs = B.chunkft_plan_cycle(tensors, 256 << 20)
     h = B.hparams(step=1, **hp)
     rows = []
-    zero = torch.zeros((), dtype=torch.float32, device=dev)
     for k, (s0, s1, numel, cost) in enumerate(chunks):
         # one set of state arrays per segment, each at the line phase of its tensor rows
         work = []
@@ -391,52 +397,220 @@ def block_cycle(torch, B, dev, hp):
             state[0].copy_(Ws[t][b:e]); state[1].zero_(); state[2].zero_()
             work.append((t, b, e, state, ws))
 
-        def run_chunk():
+        def per_segment_calls():
             for (t, b, e, state, ws) in work:
                 B.chunkft_wgrad_adamw_fused(layers[t], b, e, Ws[t], state[0], state[1], state[2], h, ws=ws)
 
-        for _ in range(2):
-            run_chunk()
-        ts = []
-        for _ in range(10):
-            a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(); run_chunk(); z.record(); z.synchronize()
-            ts.append(a.elapsed_time(z))
-        ms = sorted(ts)[len(ts) // 2]
-        # the same calls replayed from a captured HIP graph (the entry points only enqueue kernels)
-        stream = torch.cuda.Stream()
-        graph = torch.cuda.CUDAGraph()
-        torch.cuda.synchronize()
-        with torch.cuda.stream(stream):
-            with torch.cuda.graph(graph, stream=stream):
-                run_chunk()
-        torch.cuda.synchronize()
-        tg = []
-        for _ in range(12):
-            a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(); graph.replay(); z.record(); z.synchronize()
-            tg.append(a.elapsed_time(z))
-        ms_graph = sorted(tg[2:])[len(tg[2:]) // 2]
-        del graph
-        alone = []
+        group = B.GroupCall([(layers[t], b, e, Ws[t], state[0], state[1], state[2]) for (t, b, e, state, ws) in work],
+                            device=dev)
+
+        def grouped_call():
+            group(h)
+
+        ms_seg = _median_ms(torch, per_segment_calls, reps=reps)
+        ms = _median_ms(torch, grouped_call, reps=reps)
+        row = {"chunk": k, "elements": numel, "launch": "chunkft_wgrad_adamw_fused_group: one call for the chunk",
+               "ms": round(ms, 4), "ms_per_segment_calls": round(ms_seg, 4)}
+        if graph:
+            # the same call replayed from a captured HIP graph (the entry points only enqueue kernels)
+            stream = torch.cuda.Stream()
+            g = torch.cuda.CUDAGraph()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(stream):
+                with torch.cuda.graph(g, stream=stream):
+                    grouped_call()
+            torch.cuda.synchronize()
+            row["ms_graph_replay"] = round(_median_ms(torch, g.replay, reps=reps), 4)
+            del g
+        seg_rows = []
         for (t, b, e, state, ws) in work:          # each segment by itself, back to back with itself
-            tt = []
-            for _ in range(6):
-                a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-                B.chunkft_wgrad_adamw_fused(layers[t], b, e, Ws[t], state[0], state[1], state[2], h, ws=ws)
-                z.record(); z.synchronize()
-                tt.append(a.elapsed_time(z))
-            alone.append(sorted(tt)[len(tt) // 2])
-        rows.append({"chunk": k, "segments": [{"tensor": shapes[t][0], "elements": e - b,
-                                               "split_k": B.chunkft_split_k(layers[t], b, e),
-                                               "ms_alone": round(alone[i], 4)}
-                                              for i, (t, b, e, state, ws) in enumerate(work)],
-                     "elements": numel, "ms": round(ms, 4), "ms_graph_replay": round(ms_graph, 4),
-                     "ns_per_kilo_element": round(ms * 1e6 / (numel / 1e3), 3),
-                     "tflops": round(2.0 * T * numel / ms / 1e9, 1), "state_gbps": round(26.0 * numel / ms / 1e6, 1)})
+            alone = _median_ms(torch, lambda: B.chunkft_wgrad_adamw_fused(layers[t], b, e, Ws[t], state[0], state[1],
+                                                                          state[2], h, ws=ws), reps=max(4, reps // 2))
+            in_f = shapes[t][2]
+            seg_rows.append({"tensor": shapes[t][0], "elements": e - b, "in": in_f if shapes[t][1] > 1 else 0,
+                             "rows": (e - 1) // in_f - b // in_f + 1,
+                             "split_k": B.chunkft_split_k(layers[t], b, e), "ms_alone": round(alone, 4)})
+        row["segments"] = seg_rows
+        row["ns_per_kilo_element"] = round(ms * 1e6 / (numel / 1e3), 3)
+        row["tflops"] = round(2.0 * T * numel / ms / 1e9, 1)
+        row["state_gbps"] = round(26.0 * numel / ms / 1e6, 1)
+        rows.append(row)
     return {"T": T, "budget_MiB": 256, "tensors": [s[0] for s in shapes], "chunks": rows,
-            "cycle_ms": round(sum(r["ms"] for r in rows), 4)}
+            "cycle_ms": round(sum(r["ms"] for r in rows), 4),
+            "cycle_ms_per_segment_calls": round(sum(r["ms_per_segment_calls"] for r in rows), 4)}
+
+
+def _median_ms(torch, fn, reps=10, warm=2):
+    for _ in range(warm):
+        fn()
+    ts = []
+    for _ in range(reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(); fn(); b.record(); b.synchronize()
+        ts.append(a.elapsed_time(b))
+    return sorted(ts)[len(ts) // 2]
+
+
+def _fused_bound_ms(T, segs):
+    """Governing bound of fused calls on segments (elements, in, row span): the larger of the MFMA time
+    of 2 T E flops and the HBM time of 26 E bytes of state plus the operands read once."""
+    fl = sum(2.0 * T * e for e, _, _ in segs)
+    by = sum(26.0 * e + 2.0 * T * (n_in + rows) for e, n_in, rows in segs)
+    t_mfma, t_hbm = fl / (PEAK_BF16_TFLOPS * 1e12) * 1e3, by / (PEAK_HBM_GBPS * 1e9) * 1e3
+    return max(t_mfma, t_hbm), ("mfma" if t_mfma >= t_hbm else "hbm"), fl, by
+
+
+def per_config(torch, B, WL, dev, hp, cfg2):
+    """Every configuration of the task's list beside the headline one, timed on device-generated
+    operands of its shapes and value scales (X ~ N(0,1), dY ~ N(0,1e-3), configs[4]: 90 % of the token
+    rows N(0,1e-4), 10 % N(0,1e-2)), median of 10 calls between HIP events on the call's stream.
+    Chunk arrays in the recommended layout; state sets are rotated where one set would stay in the
+    256 MB last-level cache between two calls."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(211775)
+    h1 = B.hparams(step=1, **hp)
+    rows = []
+
+    def operands(out_f, in_f, T, dy_scale):
+        X = torch.randn(T, in_f, device=dev, generator=gen).to(torch.bfloat16)
+        dY = (torch.randn(T, out_f, device=dev, generator=gen) * dy_scale).to(torch.bfloat16)
+        W = (torch.randn(out_f * in_f, device=dev, generator=gen) * 0.02).to(torch.bfloat16)
+        return X, dY, W
+
+    def rowspan(b, e, n_in):
+        return (e - 1) // n_in - b // n_in + 1
+
+    # ---- configs[1] again: the fused call on warm moments (a later visit of the chunk), and the AdamW
+    # pass on a gradient that is not in any cache (four gradient / state sets in rotation)
+    layer, begin, end, W, g, ws = cfg2
+    E = end - begin
+    sets = []
+    for _ in range(4):
+        st = B.chunk_state(E, begin, dev, count=4)
+        st[0].copy_(W[begin:end]); st[1].normal_(0.0, 1e-3, generator=gen); st[2].uniform_(1e-7, 1e-6, generator=gen)
+        st[3].normal_(0.0, 3e-2, generator=gen)
+        sets.append(st)
+    turn = [0]
+
+    def warm_fused():
+        turn[0] += 1
+        m_, a_, v_, _ = sets[turn[0] % 4]
+        B.chunkft_wgrad_adamw_fused(layer, begin, end, W, m_, a_, v_, B.hparams(step=2, **hp), ws=ws)
+
+    def cold_adamw():
+        turn[0] += 1
+        m_, a_, v_, g_ = sets[turn[0] % 4]
+        B.chunkft_adamw_chunk(g_, m_, a_, v_, W[begin:end], E, B.hparams(step=2, **hp))
+
+    t = _median_ms(torch, warm_fused, reps=12)
+    bound, which, fl, by = _fused_bound_ms(1024, [(E, 4096, rowspan(begin, end, 4096))])
+    rows.append({"config": 1, "case": "fused call, warm moments (step 2), state sets rotated", "ms": round(t, 4),
+                 "tflops": round(fl / t / 1e9, 1), "gbps": round(by / t / 1e6, 1), "bound": which,
+                 "frac_of_bound": round(bound / t, 4)})
+    t = _median_ms(torch, cold_adamw, reps=12)
+    rows.append({"config": 1, "case": "AdamW pass, gradient and state not in any cache (four sets rotated)",
+                 "ms": round(t, 4), "gbps": round(30.0 * E / t / 1e6, 1), "bound": "hbm",
+                 "frac_of_bound": round(30.0 * E / t / 1e6 / PEAK_HBM_GBPS, 4)})
+    del sets
+    torch.cuda.empty_cache()
+
+    # ---- configs[2]: the transformer block, one cycle under a 256 MiB budget
+    blk = block_cycle(torch, B, dev, hp, reps=6, graph=False)
+    for ch in blk["chunks"]:
+        segs = [(sg["elements"], sg["in"], sg["rows"]) for sg in ch["segments"] if sg["in"] > 0]
+        bound, which, fl, by = _fused_bound_ms(blk["T"], segs)
+        rows.append({"config": 2, "case": "block cycle, 256 MiB budget, chunk %d: %s" % (
+                         ch["chunk"], " ".join("%s[%d]" % (sg["tensor"], sg["elements"]) for sg in ch["segments"])),
+                     "launch": ch["launch"], "ms": ch["ms"], "ms_one_call_per_segment": ch["ms_per_segment_calls"],
+                     "tflops": round(fl / ch["ms"] / 1e9, 1), "gbps": round(by / ch["ms"] / 1e6, 1), "bound": which,
+                     "frac_of_bound": round(bound / ch["ms"], 4)})
+
+    # ---- configs[3]: 70B-shaped MLP, T = 8192
+    T, hdim, ff = 8192, 8192, 28672
+    ops = {0: ("gate 28672x8192", ff, hdim) + operands(ff, hdim, T, 1e-3),
+           1: ("down 8192x28672", hdim, ff) + operands(hdim, ff, T, 1e-3)}
+    chunks = WL.config4_chunks(ff * hdim, hdim, ff * hdim)
+    off = WL.draw_offset(WL.rng_for(4, 2), ff * hdim, 64 << 20, hdim)
+    cases = [("gate, 128 MiB chunk at a seeded mid-row offset", [(0, off, off + (64 << 20))]),
+             ("128 MiB chunk at the seeded offset of the [gate | down] space", chunks["seeded"]),
+             ("128 MiB chunk straddling gate -> down", chunks["straddling"]),
+             ("1 GiB budget: gate and down whole (896 MiB)", chunks["whole"])]
+    for label, segs in cases:
+        work = []
+        for (ti, b, e) in segs:
+            name, out_f, in_f, X, dY, Wt = ops[ti]
+            lay = B.make_layer(B.LINEAR, X, dY, out_f, in_f)
+            st = B.chunk_state(e - b, b, dev)
+            st[0].copy_(Wt[b:e]); st[1].zero_(); st[2].zero_()
+            gg = B.chunk_array(e - b, b, dev)
+            nws = B.chunkft_workspace_bytes(lay, b, e)
+            wsp = torch.empty(max(nws // 4, 1), dtype=torch.float32, device=dev) if nws else None
+            work.append((lay, b, e, Wt, st, gg, wsp, in_f, B.chunkft_split_k(lay, b, e)))
+
+        def fused_all():
+            for (lay, b, e, Wt, st, gg, wsp, _, _) in work:
+                B.chunkft_wgrad_adamw_fused(lay, b, e, Wt, st[0], st[1], st[2], h1, ws=wsp)
+
+        def wgrad_all():
+            for (lay, b, e, Wt, st, gg, wsp, _, _) in work:
+                B.chunkft_chunk_wgrad(lay, b, e, gg, ws=wsp)
+
+        tf_, tw_ = _median_ms(torch, fused_all, reps=6), _median_ms(torch, wgrad_all, reps=6)
+        bound, which, fl, by = _fused_bound_ms(T, [(e - b, in_f, rowspan(b, e, in_f)) for (_, b, e, _, _, _, _, in_f, _) in work])
+        rows.append({"config": 3, "case": label, "segments": len(work), "split_k": [w[8] for w in work],
+                     "fused_ms": round(tf_, 4), "fused_tflops": round(fl / tf_ / 1e9, 1), "bound": which,
+                     "frac_of_bound": round(bound / tf_, 4), "wgrad_ms": round(tw_, 4),
+                     "wgrad_tflops": round(fl / tw_ / 1e9, 1),
+                     "wgrad_pct_mfma_peak": round(100 * fl / tw_ / 1e9 / PEAK_BF16_TFLOPS, 2)})
+        del work
+        torch.cuda.empty_cache()
+    del ops
+    torch.cuda.empty_cache()
+
+    # ---- configs[4]: lm_head shape, T = 4096, per chunk size
+    T, vocab, dim = 4096, 128256, 4096
+    X = torch.randn(T, dim, device=dev, generator=gen).to(torch.bfloat16)
+    scale = torch.where(torch.rand(T, 1, device=dev, generator=gen) < 0.1, 1e-2, 1e-4)
+    dY = (torch.randn(T, vocab, device=dev, generator=gen) * scale).to(torch.bfloat16)
+    Wt = (torch.randn(vocab * dim, device=dev, generator=gen) * 0.02).to(torch.bfloat16)
+    lay = B.make_layer(B.LINEAR, X, dY, vocab, dim)
+
+    class _Shape:                        # what config5_ranges needs of a layer
+        numel, n_in = vocab * dim, dim
+
+    for mib, (b, e) in zip(WL.CONFIG5_CHUNK_MIB, WL.config5_ranges(_Shape)):
+        E5 = e - b
+        n_sets = max(1, min(16, int((1 << 30) // (16 * E5))))
+        sets = []
+        for _ in range(n_sets):
+            st = B.chunk_state(E5, b, dev, count=4)
+            st[0].copy_(Wt[b:e]); st[1].zero_(); st[2].zero_()
+            sets.append(st)
+        nws = B.chunkft_workspace_bytes(lay, b, e)
+        wsp = torch.empty(max(nws // 4, 1), dtype=torch.float32, device=dev) if nws else None
+        turn = [0]
+
+        def fused5():
+            turn[0] += 1
+            m_, a_, v_, _ = sets[turn[0] % n_sets]
+            B.chunkft_wgrad_adamw_fused(lay, b, e, Wt, m_, a_, v_, h1, ws=wsp)
+
+        def wgrad5():
+            turn[0] += 1
+            B.chunkft_chunk_wgrad(lay, b, e, sets[turn[0] % n_sets][3], ws=wsp)
+
+        reps = max(10, 2 * n_sets)
+        tf_, tw_ = _median_ms(torch, fused5, reps=reps), _median_ms(torch, wgrad5, reps=reps)
+        bound, which, fl, by = _fused_bound_ms(T, [(E5, dim, rowspan(b, e, dim))])
+        rows.append({"config": 4, "case": "lm_head 128256x4096, %d MiB chunk at a seeded mid-row offset" % mib,
+                     "split_k": B.chunkft_split_k(lay, b, e), "state_sets_rotated": n_sets,
+                     "fused_ms": round(tf_, 4), "fused_tflops": round(fl / tf_ / 1e9, 1),
+                     "fused_gbps": round(by / tf_ / 1e6, 1), "bound": which, "frac_of_bound": round(bound / tf_, 4),
+                     "wgrad_ms": round(tw_, 4), "wgrad_tflops": round(fl / tw_ / 1e9, 1),
+                     "wgrad_pct_mfma_peak": round(100 * fl / tw_ / 1e9 / PEAK_BF16_TFLOPS, 2)})
+        del sets
+        torch.cuda.empty_cache()
+    return rows
 
 
 def sweep(torch, B, dev, hp):

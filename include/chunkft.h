@@ -324,6 +324,52 @@ int chunkft_wgrad_adamw_fused(const chunkft_layer* L, int64_t begin, int64_t end
                               void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Fused call for all segments of a chunk at once
+ *
+ * Paper: Algorithm 1 line 18 runs ONE chunk-aware backward over all slices of the
+ * active chunk C_k, and lines 19-21 one update of the chunk; a chunk that crosses
+ * tensors has one segment per tensor (chunkft_plan_cycle).  This call takes them
+ * together: the tiles of all bf16 matrix segments and the blocks of all bf16 VECTOR
+ * segments become the work items of a single kernel launch (12 segments per launch),
+ * so that a small segment (a k or v projection, a norm vector) shares the device
+ * with the large ones instead of running alone on a fraction of it.
+ * Each segment's result is, bit for bit, that of chunkft_wgrad_adamw_fused on it
+ * with the same token split.  The split: a matrix segment with split_k = 0 takes one
+ * slab when the group's matrix segments together have more 256 x 256 tiles than a
+ * quarter of the compute units (the single call's rule applied to the sum), else
+ * what the single call would choose; split_k >= 1 is obeyed.  Segments the one-launch
+ * kernel cannot take (fp32, more than one token slab, shapes off the MFMA path, bodies
+ * of a few rows, EMBEDDING / RMSNORM / LAYERNORM) are run by themselves inside this
+ * call, one after the other on `stream`, sharing `ws`.
+ *
+ * segs (host, in)   n_segs >= 1 (at most 4096) segments; ranges on the same tensor
+ *                   must not overlap, and no two segments may share state elements.
+ *   layer           operands of the tensor's backward step (as for the single call)
+ *   begin, end      flat range on that tensor
+ *   W               (device) tensor base or NULL
+ *   master, m, v    (device) chunk-local arrays ALREADY offset to the segment
+ *                   (state + chunk_off), end - begin floats each
+ * hp                one set of hyper-parameters and one step count for the chunk
+ * ws (device)       at least chunkft_group_workspace_bytes(), 16-byte aligned; may be
+ *                   NULL when that is 0 (always, when the kernel takes every segment)
+ * Errors: those of chunkft_wgrad_adamw_fused, for the first segment that has one.
+ * ---------------------------------------------------------------------- */
+typedef struct {
+  chunkft_layer layer;
+  int64_t begin, end;
+  void* W;
+  float* master;
+  float* m;
+  float* v;
+} chunkft_group_segment;
+
+size_t chunkft_group_workspace_bytes(const chunkft_group_segment* segs, int32_t n_segs);   /* host only */
+
+int chunkft_wgrad_adamw_fused_group(const chunkft_group_segment* segs, int32_t n_segs,
+                                    const chunkft_adamw_hparams* hp,
+                                    void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * The fused call without a workspace argument
  *
  * For callers that cannot allocate device memory or have none to hand over: code

@@ -72,6 +72,11 @@ class Layer(C.Structure):
                 ("norm_eps", C.c_double)]
 
 
+class GroupSegment(C.Structure):
+    _fields_ = [("layer", Layer), ("begin", C.c_int64), ("end", C.c_int64), ("W", C.c_void_p),
+                ("master", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p)]
+
+
 class ScheduleEntry(C.Structure):
     _fields_ = [("active", C.c_int32), ("load_before", C.c_int32), ("offload_after", C.c_int32),
                 ("reserved", C.c_int32), ("local_step", C.c_int64)]
@@ -116,6 +121,11 @@ def lib() -> C.CDLL:
                                                 C.c_void_p, C.c_void_p, C.c_void_p,
                                                 C.POINTER(AdamWHparams), C.c_void_p, C.c_size_t,
                                                 C.c_void_p]
+        L.chunkft_group_workspace_bytes.restype = C.c_size_t
+        L.chunkft_group_workspace_bytes.argtypes = [C.POINTER(GroupSegment), C.c_int32]
+        L.chunkft_wgrad_adamw_fused_group.restype = C.c_int
+        L.chunkft_wgrad_adamw_fused_group.argtypes = [C.POINTER(GroupSegment), C.c_int32, C.POINTER(AdamWHparams),
+                                                      C.c_void_p, C.c_size_t, C.c_void_p]
         L.chunkft_wgrad_adamw_fused_static.restype = C.c_int
         L.chunkft_wgrad_adamw_fused_static.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64, C.c_void_p,
                                                        C.c_void_p, C.c_void_p, C.c_void_p,
@@ -150,7 +160,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("chunkft_plan_cycle", "chunkft_plan_stats", "chunkft_split_k", "chunkft_workspace_bytes", "chunkft_chunk_wgrad",
            "chunkft_adamw_chunk", "chunkft_wgrad_adamw_fused", "chunkft_wgrad_adamw_fused_static",
-           "chunkft_status_string",
+           "chunkft_wgrad_adamw_fused_group", "chunkft_group_workspace_bytes", "chunkft_status_string",
            "chunkft_version", "chunkft_calib_mfma_bf16", "chunkft_calib_mfma_bf16_shape", "chunkft_schedule_at",
            "chunkft_mover_create", "chunkft_mover_destroy", "chunkft_mover_load", "chunkft_mover_await_load",
            "chunkft_mover_offload", "chunkft_mover_sync")
@@ -328,6 +338,33 @@ CALIB_SCRATCH_BYTES = 4096
 def _calib_scratch():
     import torch
     return torch.empty(CALIB_SCRATCH_BYTES, dtype=torch.uint8, device="cuda")
+
+
+class GroupCall:
+    """The segments of one chunk marshalled once for chunkft_wgrad_adamw_fused_group.
+    segments: (layer, begin, end, W, master, m, v) with the state arrays already offset to the segment.
+    Keeps the tensors alive and allocates the workspace the call asks for (usually none)."""
+
+    def __init__(self, segments, device="cuda", workspace=None):
+        import torch
+        self._keep = list(segments)
+        n = len(self._keep)
+        self.n = n
+        self.arr = (GroupSegment * max(n, 1))()
+        for i, (layer, begin, end, W, master, m, v) in enumerate(self._keep):
+            self.arr[i] = GroupSegment(layer, begin, end, _ptr(W), _ptr(master), _ptr(m), _ptr(v))
+        self.ws_bytes = lib().chunkft_group_workspace_bytes(self.arr, n) if n else 0
+        self.ws = workspace
+        if self.ws is None and self.ws_bytes:
+            self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+
+    def __call__(self, hp: AdamWHparams, stream=None, check: bool = True) -> int:
+        ws_bytes = 0 if self.ws is None else self.ws.numel() * self.ws.element_size()
+        st = lib().chunkft_wgrad_adamw_fused_group(self.arr, self.n, C.byref(hp), _ptr(self.ws), ws_bytes,
+                                                   _stream_ptr(stream))
+        if check and st != OK:
+            raise ChunkFTError(st, "chunkft_wgrad_adamw_fused_group")
+        return st
 
 
 def chunkft_wgrad_adamw_fused_static(layer: Layer, begin: int, end: int, W, master, m, v, hp: AdamWHparams,

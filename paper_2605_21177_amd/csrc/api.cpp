@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdint>
 #include <limits>
+#include <vector>
 
 #include "internal.h"
 
@@ -180,36 +181,169 @@ extern "C" int chunkft_adamw_chunk(const float* g, float* master, float* m, floa
   return launch_adamw(g, n, s, W_at_begin, stream) == 0 ? CHUNKFT_OK : CHUNKFT_ERR_HIP;
 }
 
+namespace {
+
+// Pointer checks of the fused calls (after the layer and the range were accepted).
+int check_fused_pointers(const chunkft_layer* L, const void* W, const float* master, const float* m, const float* v) {
+  if (!master || !m || !v) return CHUNKFT_ERR_INVALID_ARG;
+  const uintptr_t al = reinterpret_cast<uintptr_t>(master) | reinterpret_cast<uintptr_t>(m) |
+                       reinterpret_cast<uintptr_t>(v);
+  if (al & 3u) return CHUNKFT_ERR_INVALID_ARG;
+  if (W && (reinterpret_cast<uintptr_t>(W) & (L->dtype == CHUNKFT_F32 ? 3u : 1u))) return CHUNKFT_ERR_INVALID_ARG;
+  return CHUNKFT_OK;
+}
+
+Sinks fused_sinks(const chunkft_layer* L, void* W, float* master, float* m, float* v, const AdamWConsts& consts) {
+  Sinks s{};
+  s.c = consts;
+  s.master = master;
+  s.m = m;
+  s.v = v;
+  s.W = W;
+  s.w_kind = !W ? W_NONE : (L->dtype == CHUNKFT_BF16 ? W_BF16 : W_F32);
+  return s;
+}
+
+// One validated fused call: the kernels of a segment by itself.
+int run_fused(const chunkft_layer* L, const Checked& c, Sinks s, void* ws, void* stream) {
+  s.ws = static_cast<float*>(ws);
+  if (c.p.S > 1) place_partials(s, c.p, ws, s.master);
+  if (c.p.S <= 1) return run_wgrad(L, c, EMIT_ADAMW, s, stream);
+  const int r = run_wgrad(L, c, EMIT_PARTIAL, s, stream);
+  if (r != CHUNKFT_OK) return r;
+  void* w_at = nullptr;
+  if (s.W) w_at = static_cast<char*>(s.W) + static_cast<size_t>(c.p.begin) * (L->dtype == CHUNKFT_BF16 ? 2u : 4u);
+  return launch_reduce(s.ws, c.p.S, c.p.end - c.p.begin, EMIT_ADAMW, s, w_at, stream) == 0 ? CHUNKFT_OK
+                                                                                        : CHUNKFT_ERR_HIP;
+}
+
+}  // namespace
+
 extern "C" int chunkft_wgrad_adamw_fused(const chunkft_layer* L, int64_t begin, int64_t end, void* W,
                                          float* master, float* m, float* v,
                                          const chunkft_adamw_hparams* hp, void* ws, size_t ws_bytes,
                                          void* stream) {
   const Checked c = check_layer(L, begin, end);
   if (c.status != CHUNKFT_OK) return c.status;
-  if (!master || !m || !v) return CHUNKFT_ERR_INVALID_ARG;
-  const uintptr_t al = reinterpret_cast<uintptr_t>(master) | reinterpret_cast<uintptr_t>(m) |
-                       reinterpret_cast<uintptr_t>(v);
-  if (al & 3u) return CHUNKFT_ERR_INVALID_ARG;
-  if (W && (reinterpret_cast<uintptr_t>(W) & (L->dtype == CHUNKFT_F32 ? 3u : 1u))) return CHUNKFT_ERR_INVALID_ARG;
-  Sinks s{};
-  const int hr = check_hparams(hp, &s.c);
+  const int pr = check_fused_pointers(L, W, master, m, v);
+  if (pr != CHUNKFT_OK) return pr;
+  AdamWConsts consts;
+  const int hr = check_hparams(hp, &consts);
   if (hr != CHUNKFT_OK) return hr;
   const int wsr = check_workspace(L, c.p, ws, ws_bytes);
   if (wsr != CHUNKFT_OK) return wsr;
-  s.master = master;
-  s.m = m;
-  s.v = v;
-  s.W = W;
-  s.w_kind = !W ? W_NONE : (L->dtype == CHUNKFT_BF16 ? W_BF16 : W_F32);
-  s.ws = static_cast<float*>(ws);
-  if (c.p.S > 1) place_partials(s, c.p, ws, master);
-  if (c.p.S <= 1) return run_wgrad(L, c, EMIT_ADAMW, s, stream);
-  const int r = run_wgrad(L, c, EMIT_PARTIAL, s, stream);
-  if (r != CHUNKFT_OK) return r;
-  void* w_at = nullptr;
-  if (W) w_at = static_cast<char*>(W) + static_cast<size_t>(begin) * (L->dtype == CHUNKFT_BF16 ? 2u : 4u);
-  return launch_reduce(s.ws, c.p.S, end - begin, EMIT_ADAMW, s, w_at, stream) == 0 ? CHUNKFT_OK
-                                                                                   : CHUNKFT_ERR_HIP;
+  return run_fused(L, c, fused_sinks(L, W, master, m, v, consts), ws, stream);
+}
+
+namespace {
+
+constexpr int32_t kMaxGroupSegments = 4096;
+
+struct GroupPlan {
+  int status = CHUNKFT_OK;
+  std::vector<Checked> checked;       // per segment
+  std::vector<char> grouped;          // 1: goes into the one-launch kernel
+  size_t ws_need = 0;                 // the largest need of a segment that runs by itself
+  bool large_tile = false;
+};
+
+// Validates every segment and decides which ones the one-launch kernel takes.  Matrix segments
+// whose split_k is 0 take one token slab when the group as a whole has the tiles to fill the
+// device (more than a quarter of its compute units, the rule of the single call, applied to the
+// sum); a segment the kernel cannot take (fp32, a forced split, a shape off the MFMA path, a body
+// of a few rows, the other kinds) runs by itself, exactly as chunkft_wgrad_adamw_fused would.
+GroupPlan plan_group(const chunkft_group_segment* segs, int32_t n) {
+  GroupPlan g;
+  g.checked.resize(static_cast<size_t>(n));
+  g.grouped.assign(static_cast<size_t>(n), 0);
+  const int cus = device_compute_units();
+  int64_t tiles = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    const chunkft_group_segment& sg = segs[i];
+    Checked& c = g.checked[static_cast<size_t>(i)];
+    c = check_layer(&sg.layer, sg.begin, sg.end);
+    if (c.status != CHUNKFT_OK) { g.status = c.status; return g; }
+    const int pr = check_fused_pointers(&sg.layer, sg.W, sg.master, sg.m, sg.v);
+    if (pr != CHUNKFT_OK) { g.status = pr; return g; }
+    if (c.mfma && sg.layer.split_k == 0) {
+      const RowSplit rs = split_rows(c.p);
+      const int64_t rows = rs.rb1 > rs.rb0 ? rs.rb1 - rs.rb0 : 0;
+      const int64_t t = ((rows + kMainTileM - 1) / kMainTileM) * ((c.p.in + kMainTileN - 1) / kMainTileN);
+      tiles = tiles > (int64_t(1) << 40) ? tiles : tiles + t;
+    }
+  }
+  const bool full = tiles > cus / 4;
+  bool any = false, all_large = true;
+  for (int32_t i = 0; i < n; ++i) {
+    const chunkft_group_segment& sg = segs[i];
+    Checked& c = g.checked[static_cast<size_t>(i)];
+    const bool vec = sg.layer.kind == CHUNKFT_VECTOR && sg.layer.dtype == CHUNKFT_BF16;
+    bool take = vec;
+    if (c.mfma && (sg.layer.split_k == 1 || (sg.layer.split_k == 0 && full))) {
+      c.p.S = 1;
+      c.p.kslab = (c.p.T + kMainTileK - 1) / kMainTileK * kMainTileK;
+      take = group_takes_segment(c.p, false);
+      if (!take) {                                     // back to what the single call would do
+        const Split sp = pick_split(sg.layer.kind, sg.layer.dtype, sg.layer.out, sg.layer.in, sg.layer.T, sg.begin,
+                                    sg.end, sg.layer.split_k, c.mfma, cus);
+        c.p.S = sp.S;
+        c.p.kslab = sp.kslab;
+      }
+    }
+    g.grouped[static_cast<size_t>(i)] = take ? 1 : 0;
+    if (take && !vec) {
+      any = true;
+      all_large = all_large && fused_takes_large_tile(c.p);
+    }
+    if (!take) {
+      const size_t need = workspace_need(&sg.layer, c.p);
+      if (need > g.ws_need) g.ws_need = need;
+    }
+  }
+  g.large_tile = any && all_large;
+  return g;
+}
+
+}  // namespace
+
+extern "C" size_t chunkft_group_workspace_bytes(const chunkft_group_segment* segs, int32_t n_segs) {
+  if (!segs || n_segs < 1 || n_segs > kMaxGroupSegments) return 0;
+  const GroupPlan g = plan_group(segs, n_segs);
+  return g.status == CHUNKFT_OK ? g.ws_need : 0;
+}
+
+extern "C" int chunkft_wgrad_adamw_fused_group(const chunkft_group_segment* segs, int32_t n_segs,
+                                               const chunkft_adamw_hparams* hp, void* ws, size_t ws_bytes,
+                                               void* stream) {
+  if (!segs || n_segs < 1 || n_segs > kMaxGroupSegments) return CHUNKFT_ERR_INVALID_ARG;
+  AdamWConsts consts;
+  const int hr = check_hparams(hp, &consts);
+  if (hr != CHUNKFT_OK) return hr;
+  const GroupPlan g = plan_group(segs, n_segs);
+  if (g.status != CHUNKFT_OK) return g.status;
+  if (g.ws_need > 0 && (!ws || ws_bytes < g.ws_need || (reinterpret_cast<uintptr_t>(ws) & 15u)))
+    return CHUNKFT_ERR_WORKSPACE;
+  std::vector<GroupSegment> table;
+  table.reserve(static_cast<size_t>(n_segs));
+  for (int32_t i = 0; i < n_segs; ++i) {
+    if (!g.grouped[static_cast<size_t>(i)]) continue;
+    const chunkft_group_segment& sg = segs[i];
+    GroupSegment t{};
+    t.p = g.checked[static_cast<size_t>(i)].p;
+    t.s = fused_sinks(&sg.layer, sg.W, sg.master, sg.m, sg.v, consts);
+    t.vector = sg.layer.kind == CHUNKFT_VECTOR;
+    if (t.vector) { t.p.S = 1; t.p.kslab = t.p.T; }
+    table.push_back(t);
+  }
+  if (launch_fused_group(table.data(), static_cast<int>(table.size()), g.large_tile, stream) != 0) return CHUNKFT_ERR_HIP;
+  for (int32_t i = 0; i < n_segs; ++i) {
+    if (g.grouped[static_cast<size_t>(i)]) continue;
+    const chunkft_group_segment& sg = segs[i];
+    const int r = run_fused(&sg.layer, g.checked[static_cast<size_t>(i)],
+                            fused_sinks(&sg.layer, sg.W, sg.master, sg.m, sg.v, consts), ws, stream);
+    if (r != CHUNKFT_OK) return r;
+  }
+  return CHUNKFT_OK;
 }
 
 extern "C" const char* chunkft_status_string(int status) {

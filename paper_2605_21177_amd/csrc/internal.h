@@ -63,6 +63,7 @@ struct RowSplit {
   int64_t trail_row;    // partial last row outside the body, or -1
 };
 RowSplit split_rows(const WgradProblem& p);               // needs p.begin, p.end, p.in only
+bool edge_rows_folded(const RowSplit& rs);                // the MFMA kernel carries the edge rows itself
 
 // Tile of the plain MFMA gradient and of the FMA kernel: what the token split is chosen from.
 constexpr int64_t kMainTileM = 256, kMainTileN = 256, kMainTileK = 32;
@@ -76,6 +77,23 @@ int device_compute_units();                               // of the current devi
 bool mfma_path_ok(const WgradProblem& p);                 // alignment / shape rules of the MFMA kernel
 Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T, int64_t begin,
                  int64_t end, int32_t forced, bool mfma, int compute_units);
+
+// The fused call takes the 256 x 256 tile (one workgroup per compute unit) instead of the 128 x 256
+// one (two per compute unit) when it is compute-bound and its operands are too large to stay in
+// the last-level cache (shape.cpp).
+bool fused_takes_large_tile(const WgradProblem& p);
+
+// One segment of a grouped fused call: a bf16 matrix segment for the MFMA kernel (S = 1) or a
+// bf16 scale-vector segment whose normalised input the caller supplies.
+struct GroupSegment {
+  WgradProblem p;
+  Sinks s;
+  bool vector;
+};
+// Whether the one-launch kernel can take this segment (else the caller runs it by itself).
+bool group_takes_segment(const WgradProblem& p, bool vector);
+// All segments in as few launches as the kernel's argument table allows (12 segments each).
+int launch_fused_group(const GroupSegment* segs, int n, bool large_tile, void* stream);
 
 // All launchers return a hipError_t as int (0 = success).
 int launch_wgrad_bf16_mfma(const WgradProblem& p, int mode, const Sinks& s, void* stream);

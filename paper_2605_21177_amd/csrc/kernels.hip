@@ -22,6 +22,7 @@
 
 #include <atomic>
 #include <cstdint>
+#include <cstdlib>
 
 #include "internal.h"
 
@@ -477,28 +478,8 @@ __device__ __forceinline__ void tile_epilogue(const MfmaParams& q, unsigned char
 // wave waited for its own loads of it) and retires slab kt, whose ring slot the
 // loads of slab kt+NS then overwrite -- the whole ring is in flight.
 template <class C, int MODE>
-__global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q) {
-  extern __shared__ __attribute__((aligned(1024))) unsigned char ldsb[];
+__device__ __forceinline__ void mfma_tile(const MfmaParams& q, const int item, unsigned char* ldsb) {
   const WgradProblem& p = q.p;
-
-  // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD one
-  // contiguous run of work items so that tiles sharing dY rows / X columns
-  // meet in the same L2.
-  const int n_items = q.n_tile_items;
-  const int per_xcd = (n_items + 7) >> 3;
-  const int item = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-  if (item >= n_items) return;
-
-  // Two workgroups share a compute unit.  Started together they run their MFMA loops
-  // together and then their HBM-bound epilogues together; with q.stagger > 0 the second
-  // one of each pair (workgroups are dealt to the 32 compute units of an XCD in order:
-  // the first 32 fill one slot each, the next 32 the other) starts late instead, so that
-  // one tends to be in its loop while the other is in its epilogue.
-  if constexpr (C::WM == 1) {
-    const int j = (int)(blockIdx.x >> 3);
-    if (j >= 32 && j < 64)
-      for (int i = 0; i < q.stagger; ++i) __builtin_amdgcn_s_sleep(127);
-  }
 
   // ---- which tile, which token slab
   const int n_tiles = q.tiles_m * q.tiles_n;
@@ -851,6 +832,119 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaParams q
   if (has_edge) run_slabs(IntC<1>{}); else run_slabs(IntC<0>{});
 
   tile_epilogue<C, MODE>(q, ldsb, row0, col0, slab, wave, lane, tid, acc, has_edge, edge_blk, acc_e);
+}
+
+// Workgroup ids are dealt round-robin to the 8 XCDs; each XCD gets one contiguous run of work
+// items so that tiles sharing dY rows / X columns meet in the same L2.  Returns -1 for the
+// padding workgroups at the end of the grid.
+__device__ __forceinline__ int xcd_work_item(int n_items) {
+  const int per_xcd = (n_items + 7) >> 3;
+  const int item = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  return item < n_items ? item : -1;
+}
+
+// Two workgroups share a compute unit.  Started together they run their MFMA loops
+// together and then their HBM-bound epilogues together; with stagger > 0 the second
+// one of each pair (workgroups are dealt to the 32 compute units of an XCD in order:
+// the first 32 fill one slot each, the next 32 the other) starts late instead, so that
+// one tends to be in its loop while the other is in its epilogue.  With one workgroup per
+// compute unit (the large tile, fused call only) every second compute unit starts late.
+template <class C, int MODE>
+__device__ __forceinline__ void start_offset(int stagger) {
+  const int j = (int)(blockIdx.x >> 3);
+  bool late = false;
+  if constexpr (C::WM == 1) late = j >= 32 && j < 64;
+  else if constexpr (MODE == EMIT_ADAMW) late = j < 32 && (j & 1);
+  if (late)
+    for (int i = 0; i < stagger; ++i) __builtin_amdgcn_s_sleep(127);
+}
+
+// The parameters stay in the kernel-argument memory and are read where they are used (the index
+// below is always 0, which the compiler cannot know): taken by value they are all loaded into scalar
+// registers up front, and the loop then runs out of registers (14 spilled vector registers in the
+// 128 x 256 configuration against 2).
+struct MfmaArgs {
+  MfmaParams q[1];
+};
+
+template <class C, int MODE>
+__global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaArgs args) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char ldsb[];
+  const MfmaParams& q = args.q[blockIdx.y];
+  const int n_items = q.n_tile_items;
+  const int per_xcd = (n_items + 7) >> 3;
+  const int item = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  if (item >= n_items) return;
+  if constexpr (C::WM == 1) {
+    const int j = (int)(blockIdx.x >> 3);
+    if (j >= 32 && j < 64)
+      for (int i = 0; i < q.stagger; ++i) __builtin_amdgcn_s_sleep(127);
+  } else if constexpr (MODE == EMIT_ADAMW) {
+    const int j = (int)(blockIdx.x >> 3);
+    if (j < 32 && (j & 1))
+      for (int i = 0; i < q.stagger; ++i) __builtin_amdgcn_s_sleep(127);
+  }
+  mfma_tile<C, MODE>(q, item, ldsb);
+}
+
+// ---------------------------------------------------------------------------
+// one launch for all segments of a chunk (fused call only)
+// ---------------------------------------------------------------------------
+// The work items of up to kGroupMax segments are laid end to end: the tiles of each bf16 matrix
+// segment (parameters as for wgrad_mfma_kernel) and, for a bf16 scale-vector segment (tiles_m = 0),
+// blocks of 64 elements.  A workgroup finds its segment by its item number and then does exactly
+// what the single-segment kernels do, in the same order, so the results are theirs bit for bit.
+constexpr int kGroupMax = 12;
+
+struct GroupParams {
+  int32_t n_segs, n_items, stagger, reserved;
+  int32_t item_start[kGroupMax + 1];     // first work item of each segment; [n_segs] = n_items
+  MfmaParams seg[kGroupMax];
+};
+static_assert(sizeof(GroupParams) <= 4096, "the table travels as a kernel argument");
+
+// 64 elements of a scale-vector segment: the arithmetic of colsum_kernel (16 token groups, each summed
+// in ascending token order, then added in group order), with the workgroup's waves taking the token
+// groups in turn.
+template <class C, int MODE>
+__device__ __forceinline__ void colsum_item(const MfmaParams& q, const int block, unsigned char* ldsb) {
+  constexpr int TG = 16;
+  float (*red)[64] = reinterpret_cast<float (*)[64]>(ldsb);
+  const WgradProblem& p = q.p;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t j = p.begin + (int64_t)block * 64 + lane;
+  const unsigned short* dY = (const unsigned short*)p.dY;
+  const unsigned short* X = (const unsigned short*)p.X;
+  for (int tg = wave; tg < TG; tg += C::NW) {
+    float acc = 0.f;
+    if (j < p.end)
+#pragma unroll 8
+      for (int64_t t = tg; t < p.T; t += TG) {
+        const float x = bf16_bits_to_f32(X[t * p.ldx + j]);
+        acc = fmaf(bf16_bits_to_f32(dY[t * p.lddy + j]), x, acc);
+      }
+    red[tg][lane] = acc;
+  }
+  __syncthreads();
+  if (wave == 0 && j < p.end) {
+    float sum = red[0][lane];
+    for (int g = 1; g < TG; ++g) sum += red[g][lane];
+    emit<MODE>(q.s, p.end - p.begin, 0, j - p.begin, j, sum);
+  }
+}
+
+template <class C>
+__global__ __launch_bounds__(C::NT, 2) void wgrad_group_kernel(const GroupParams gp) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char ldsb[];
+  const int item = xcd_work_item(gp.n_items);
+  if (item < 0) return;
+  start_offset<C, EMIT_ADAMW>(gp.stagger);
+  int si = 0;
+  while (si + 1 < gp.n_segs && item >= gp.item_start[si + 1]) ++si;
+  const MfmaParams& q = gp.seg[si];
+  const int local = item - gp.item_start[si];
+  if (q.tiles_m == 0) colsum_item<C, EMIT_ADAMW>(q, local, ldsb);
+  else mfma_tile<C, EMIT_ADAMW>(q, local, ldsb);
 }
 
 // ---------------------------------------------------------------------------
@@ -1302,6 +1396,10 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // 200 us at 8, 208 us at 0), flat between 6 and 10 for 4096 and 8192; the plain gradient gains
 // nothing.
 constexpr int kStaggerAdamW = 6;
+// The large tile has one workgroup per compute unit: there every second compute unit of an XCD starts
+// late, so that the epilogues of half the part fall into the loops of the other half (measured at
+// T = 8192: 1 - 3 % at 10, nothing from 24 on).
+constexpr int kStaggerAdamWLarge = 10;
 using MainCfg = RingCfg<2, 4>;    // 256 x 256 tiles, four slabs of 33 KB in LDS, one workgroup per compute unit
 using FusedCfg = RingCfg<1, 3>;   // 128 x 256 tiles, three slabs of 25 KB, two workgroups per compute unit
                                   // (the fused call, and plain gradients with few tiles)
@@ -1320,7 +1418,9 @@ int launch_mfma_mode(const MfmaParams& q, int grid, hipStream_t st) {
     if (e != hipSuccess) return (int)e;
     if (dev >= 0 && dev < kMaxDevices) attr_set[dev].store(true, std::memory_order_release);
   }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS_BYTES, st, q);
+  MfmaArgs args;
+  args.q[0] = q;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS_BYTES, st, args);
   return (int)hipGetLastError();
 }
 
@@ -1349,31 +1449,11 @@ int device_compute_units() {
   return cus;
 }
 
+// Parameters of the MFMA kernel for a call.  False if the work items cannot be counted in 32 bits.
 template <class C>
-int launch_mfma_cfg(const WgradProblem& p, int mode, const Sinks& s, hipStream_t st) {
-  const RowSplit rs = split_rows(p);
-  // the edge rows ride in the MFMA kernel if it has the tile rows that carry them
-  // (more than 128 body rows = two tile rows of the small tile; the same rule for both tile
-  // sizes, so that the fused and the plain call sum every element in the same order)
-  const bool folded = rs.rb1 - rs.rb0 > 128;
-  if (!folded && (rs.lead_base >= 0 || rs.trail_row >= 0)) {
-    EdgeParams e{};
-    e.p = p;
-    e.s = s;
-    e.lead_base = rs.lead_base;
-    e.trail_row = rs.trail_row;
-    const dim3 grid((unsigned)ceil_div(p.in, kEdgeCols)), block(kEdgeThreads);
-    switch (mode) {
-      case EMIT_STORE: hipLaunchKernelGGL((wgrad_edge_kernel<EMIT_STORE>), grid, block, 0, st, e); break;
-      case EMIT_ACCUM: hipLaunchKernelGGL((wgrad_edge_kernel<EMIT_ACCUM>), grid, block, 0, st, e); break;
-      case EMIT_PARTIAL: hipLaunchKernelGGL((wgrad_edge_kernel<EMIT_PARTIAL>), grid, block, 0, st, e); break;
-      default: hipLaunchKernelGGL((wgrad_edge_kernel<EMIT_ADAMW>), grid, block, 0, st, e); break;
-    }
-    const int err = (int)hipGetLastError();
-    if (err != 0) return err;
-  }
-  if (rs.rb1 <= rs.rb0) return 0;
-  MfmaParams q{};
+bool fill_mfma_params(const WgradProblem& p, int mode, const Sinks& s, const RowSplit& rs, MfmaParams& q) {
+  const bool folded = edge_rows_folded(rs);
+  q = MfmaParams{};
   q.p = p;
   q.s = s;
   q.rb0 = rs.rb0;
@@ -1381,8 +1461,7 @@ int launch_mfma_cfg(const WgradProblem& p, int mode, const Sinks& s, hipStream_t
   q.lead_base = folded ? rs.lead_base : -1;
   q.trail_row = folded ? rs.trail_row : -1;
   const int64_t tiles_m = ceil_div(rs.rb1 - rs.rb0, C::BM), tiles_n = ceil_div(p.in, C::BN);
-  if (tiles_m > 0x3fffffff || tiles_n > 0x3fffffff || tiles_m * tiles_n > 0x3fffffff / p.S)
-    return (int)hipErrorInvalidValue;                  // work items are counted in 32 bits
+  if (tiles_m > 0x3fffffff || tiles_n > 0x3fffffff || tiles_m * tiles_n > 0x3fffffff / p.S) return false;
   q.tiles_m = (int32_t)tiles_m;
   q.tiles_n = (int32_t)tiles_n;
   q.n_tile_items = (int32_t)(tiles_m * tiles_n * p.S);
@@ -1391,28 +1470,110 @@ int launch_mfma_cfg(const WgradProblem& p, int mode, const Sinks& s, hipStream_t
   // for the fused call on 4096 x 14336 at T = 4096: 571 us in groups of 4 against 736 us row-major;
   // on 14336 x 4096 at T = 1024: 313 against 335 us.
   q.group_m = mode == EMIT_ADAMW ? 4 : 8;
-  q.stagger = mode == EMIT_ADAMW ? kStaggerAdamW : 0;
+  q.stagger = mode == EMIT_ADAMW ? (C::WM == 1 ? kStaggerAdamW : kStaggerAdamWLarge) : 0;
+  return true;
+}
+
+int launch_edge_rows(const WgradProblem& p, int mode, const Sinks& s, const RowSplit& rs, hipStream_t st) {
+  EdgeParams e{};
+  e.p = p;
+  e.s = s;
+  e.lead_base = rs.lead_base;
+  e.trail_row = rs.trail_row;
+  const dim3 grid((unsigned)ceil_div(p.in, kEdgeCols)), block(kEdgeThreads);
+  switch (mode) {
+    case EMIT_STORE: hipLaunchKernelGGL((wgrad_edge_kernel<EMIT_STORE>), grid, block, 0, st, e); break;
+    case EMIT_ACCUM: hipLaunchKernelGGL((wgrad_edge_kernel<EMIT_ACCUM>), grid, block, 0, st, e); break;
+    case EMIT_PARTIAL: hipLaunchKernelGGL((wgrad_edge_kernel<EMIT_PARTIAL>), grid, block, 0, st, e); break;
+    default: hipLaunchKernelGGL((wgrad_edge_kernel<EMIT_ADAMW>), grid, block, 0, st, e); break;
+  }
+  return (int)hipGetLastError();
+}
+
+template <class C>
+int launch_mfma_cfg(const WgradProblem& p, int mode, const Sinks& s, hipStream_t st) {
+  const RowSplit rs = split_rows(p);
+  if (!edge_rows_folded(rs) && (rs.lead_base >= 0 || rs.trail_row >= 0)) {
+    const int err = launch_edge_rows(p, mode, s, rs, st);
+    if (err != 0) return err;
+  }
+  if (rs.rb1 <= rs.rb0) return 0;
+  MfmaParams q;
+  if (!fill_mfma_params<C>(p, mode, s, rs, q)) return (int)hipErrorInvalidValue;   // work items are counted in 32 bits
   const int grid = (q.n_tile_items + 7) / 8 * 8;
   switch (mode) {
     case EMIT_STORE: return launch_mfma_mode<C, EMIT_STORE>(q, grid, st);
     case EMIT_ACCUM: return launch_mfma_mode<C, EMIT_ACCUM>(q, grid, st);
     case EMIT_PARTIAL: return launch_mfma_mode<C, EMIT_PARTIAL>(q, grid, st);
-    default:
-      if constexpr (C::WM == 1) return launch_mfma_mode<C, EMIT_ADAMW>(q, grid, st);
-      else return (int)hipErrorInvalidValue;   // the large tile is not built with the AdamW epilogue
+    default: return launch_mfma_mode<C, EMIT_ADAMW>(q, grid, st);
   }
 }
 
 int launch_wgrad_bf16_mfma(const WgradProblem& p, int mode, const Sinks& s, void* stream) {
   // The plain gradient (short epilogue) is a little faster on the large tile; the fused call,
   // whose epilogue moves 26 bytes per element, gains from two workgroups per compute unit.
-  if (mode == EMIT_ADAMW) return launch_mfma_cfg<FusedCfg>(p, mode, s, (hipStream_t)stream);
+  if (mode == EMIT_ADAMW) {
+    if (fused_takes_large_tile(p)) return launch_mfma_cfg<MainCfg>(p, mode, s, (hipStream_t)stream);
+    return launch_mfma_cfg<FusedCfg>(p, mode, s, (hipStream_t)stream);
+  }
   // A segment whose large tiles would occupy at most half the compute units takes the small
   // tile too: twice the workgroups, each element still summed over the tokens in the same order.
   const RowSplit rs = split_rows(p);
   const int64_t big_tiles = ceil_div(rs.rb1 - rs.rb0, MainCfg::BM) * ceil_div(p.in, MainCfg::BN) * p.S;
   if (big_tiles <= device_compute_units() / 2) return launch_mfma_cfg<FusedCfg>(p, mode, s, (hipStream_t)stream);
   return launch_mfma_cfg<MainCfg>(p, mode, s, (hipStream_t)stream);
+}
+
+// ---- grouped fused call
+template <class C>
+static int launch_group_cfg(const GroupSegment* segs, int n, hipStream_t st) {
+  static std::atomic<bool> attr_set[kMaxDevices] = {};
+  const auto kern = &wgrad_group_kernel<C>;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return (int)hipErrorInvalidDevice;
+  if (dev < 0 || dev >= kMaxDevices || !attr_set[dev].load(std::memory_order_acquire)) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)C::LDS_BYTES);
+    if (e != hipSuccess) return (int)e;
+    if (dev >= 0 && dev < kMaxDevices) attr_set[dev].store(true, std::memory_order_release);
+  }
+  for (int first = 0; first < n; first += kGroupMax) {
+    const int count = n - first < kGroupMax ? n - first : kGroupMax;
+    GroupParams gp{};
+    int64_t items = 0;
+    for (int i = 0; i < count; ++i) {
+      const GroupSegment& g = segs[first + i];
+      MfmaParams& q = gp.seg[i];
+      gp.item_start[i] = (int32_t)items;
+      if (g.vector) {
+        q = MfmaParams{};
+        q.p = g.p;
+        q.s = g.s;
+        q.tiles_m = 0;
+        items += ceil_div(g.p.end - g.p.begin, 64);
+      } else {
+        if (!fill_mfma_params<C>(g.p, EMIT_ADAMW, g.s, split_rows(g.p), q)) return (int)hipErrorInvalidValue;
+        gp.stagger = q.stagger;
+        items += q.n_tile_items;
+      }
+      if (items > 0x3fffffff) return (int)hipErrorInvalidValue;
+    }
+    if (gp.stagger == 0) gp.stagger = C::WM == 1 ? kStaggerAdamW : kStaggerAdamWLarge;
+    gp.item_start[count] = (int32_t)items;
+    gp.n_segs = count;
+    gp.n_items = (int32_t)items;
+    const int grid = (gp.n_items + 7) / 8 * 8;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS_BYTES, st, gp);
+    const int err = (int)hipGetLastError();
+    if (err != 0) return err;
+  }
+  return 0;
+}
+
+int launch_fused_group(const GroupSegment* segs, int n, bool large_tile, void* stream) {
+  if (n <= 0) return 0;
+  return large_tile ? launch_group_cfg<MainCfg>(segs, n, (hipStream_t)stream)
+                    : launch_group_cfg<FusedCfg>(segs, n, (hipStream_t)stream);
 }
 
 template <typename T>

@@ -31,6 +31,18 @@ RowSplit split_rows(const WgradProblem& p) {
   return rs;
 }
 
+// The edge rows ride in the MFMA kernel if it has the tile rows that carry them (more than 128 body
+// rows = two tile rows of the small tile; the same rule for both tile sizes, so that every call sums
+// every element in the same order).
+bool edge_rows_folded(const RowSplit& rs) { return rs.rb1 - rs.rb0 > 128; }
+
+bool group_takes_segment(const WgradProblem& p, bool vector) {
+  if (vector) return true;
+  const RowSplit rs = split_rows(p);
+  // a body for the MFMA kernel, its edge rows (if any) carried by it, one token slab
+  return p.S == 1 && rs.rb1 > rs.rb0 && (edge_rows_folded(rs) || (rs.lead_base < 0 && rs.trail_row < 0));
+}
+
 bool mfma_path_ok(const WgradProblem& p) {
   const auto a16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
   if (!(p.in % 8 == 0 && p.out % 8 == 0 && p.ldx % 8 == 0 && p.lddy % 8 == 0 && a16(p.X) && a16(p.dY)))
@@ -39,6 +51,16 @@ bool mfma_path_ok(const WgradProblem& p) {
   // the 32-bit byte offsets of the global->LDS loads: a row / column index plus up to 63 tokens
   if (p.out + 64 * p.lddy >= (int64_t(1) << 31) || p.in + 64 * p.ldx >= (int64_t(1) << 31)) return false;
   return true;
+}
+
+// Long token counts make the fused call compute-bound (2 T flops against 26 bytes per element: from
+// about 4000 tokens on), and when the operands are also too large to stay in the last-level
+// cache the large tile's third less operand traffic decides: measured at T = 8192 on the
+// 70B-shaped MLP (X of 128 and 448 MiB) 1.03 against 1.14 ms and 1.25 against 1.37 ms for a
+// 128 MiB chunk, 3.46 against 4.07 ms for the whole gate projection; with X of 64 MiB
+// (in = 4096) the two tiles are level at T = 8192 and the small one wins below.
+bool fused_takes_large_tile(const WgradProblem& p) {
+  return p.T >= 6144 && p.in >= ((int64_t(128) << 20) / 2 + p.T - 1) / p.T;
 }
 
 Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T, int64_t begin,

@@ -227,6 +227,26 @@ def config4(scale: int = 1, T: Optional[int] = None) -> List[LayerCase]:
     ]
 
 
+def config4_chunks(gate_numel: int, gate_cols: int, down_numel: int, length: int = 64 * MiB):
+    """The chunks of configuration 4 as lists of (tensor, begin, end), tensor 0 = gate, 1 = down, in
+    the concatenated [gate | down] element space: a 128 MiB chunk (`length` elements) at a seeded
+    mid-row offset, one that straddles the gate -> down boundary, and the 1 GiB budget's chunk,
+    which exceeds both tensors together and so takes each whole."""
+    rng = rng_for(4, 1)
+    off = draw_offset(rng, gate_numel + down_numel, length, gate_cols)
+    straddle = gate_numel - length // 3 - 17
+
+    def cut(o):
+        segs = []
+        if o < gate_numel:
+            segs.append((0, o, min(o + length, gate_numel)))
+        if o + length > gate_numel:
+            segs.append((1, max(o, gate_numel) - gate_numel, o + length - gate_numel))
+        return segs
+
+    return {"seeded": cut(off), "straddling": cut(straddle), "whole": [(0, 0, gate_numel), (1, 0, down_numel)]}
+
+
 def config5(scale: int = 1, T: Optional[int] = None) -> LayerCase:
     """Embedding / lm_head shape, bf16: W 128256x4096, T = 4096; 90% of the
     token rows of dY are N(0, 1e-4), 10% are N(0, 1e-2)."""

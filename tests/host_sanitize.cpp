@@ -76,6 +76,16 @@ int launch_reduce(const float* ws, int32_t S, int64_t E, int, const Sinks& s, vo
   expect(lo >= g_ws_lo && lo + 4u * (uintptr_t)((int64_t)(S - 1) * s.ws_pitch + E) <= g_ws_hi, "reduction reads inside the workspace");
   return 0;
 }
+int launch_fused_group(const GroupSegment* segs, int n, bool, void*) {
+  g_launches += n > 0;
+  for (int i = 0; i < n; ++i) {
+    check_problem(segs[i].p);
+    expect(segs[i].p.S == 1, "grouped segment with a token split");
+    expect(group_takes_segment(segs[i].p, segs[i].vector), "grouped segment the kernel cannot take");
+    if (!segs[i].vector) expect(mfma_path_ok(segs[i].p), "grouped matrix segment off the MFMA path");
+  }
+  return 0;
+}
 int launch_adamw(const float*, int64_t n, const Sinks&, void*, void*) { ++g_launches; expect(n > 0, "adamw size"); return 0; }
 }  // namespace chunkft
 
@@ -183,7 +193,57 @@ int main() {
       if ((ra == CHUNKFT_OK) != (n > 0 && hp.step >= 1 && ra == 0)) { printf("adamw validation at %d\n", it); return 1; }
     }
   }
+  // ---- grouped fused call: random groups of segments on made-up addresses
+  long groups = 0, groups_ok = 0;
+  for (int it = 0; it < 30000; ++it) {
+    const int n = 1 + (int)(rng() % 20);
+    std::vector<chunkft_group_segment> sg((size_t)n);
+    for (auto& g : sg) {
+      chunkft_layer& L = g.layer;
+      L = chunkft_layer{};
+      L.kind = rng() % 12 == 0 ? (int32_t)(rng() % 5) : (rng() % 4 == 0 ? CHUNKFT_VECTOR : CHUNKFT_LINEAR);
+      L.dtype = rng() % 8 == 0 ? CHUNKFT_F32 : CHUNKFT_BF16;
+      L.out = L.kind == CHUNKFT_LINEAR || L.kind == CHUNKFT_EMBEDDING ? 8 * (1 + (int64_t)(rng() % 600)) : 1;
+      L.in = (rng() % 10 ? 8 : 1) * (1 + (int64_t)(rng() % 600));
+      L.T = 1 + (int64_t)(rng() % 9000);
+      if (L.kind == CHUNKFT_EMBEDDING && L.T > 8192) L.T = 8192;
+      L.ldx = L.in;
+      L.lddy = L.kind == CHUNKFT_LINEAR ? L.out : L.in;
+      L.X = (const void*)(base + 16 * (rng() % 1000));
+      L.dY = (const void*)(base + 16 * (rng() % 1000));
+      L.split_k = rng() % 5 ? 0 : (int32_t)(rng() % 5);
+      if (L.kind != CHUNKFT_LINEAR) L.split_k = 0;
+      L.norm_eps = 1e-6;
+      const int64_t numel = L.out * L.in;
+      g.begin = (int64_t)(rng() % (uint64_t)numel);
+      g.end = g.begin + 1 + (int64_t)(rng() % (uint64_t)(numel - g.begin));
+      if (rng() % 400 == 0) g.end = g.begin;
+      g.W = rng() % 2 ? (void*)(base + 0x1000000u) : nullptr;
+      g.master = g.m = g.v = (float*)(base + 0x2000000u + 4 * (rng() % 64));
+      if (rng() % 500 == 0) g.m = nullptr;
+    }
+    chunkft_adamw_hparams hp{1e-4, 0.9, 0.999, 1e-8, 0.01, 1 + (int64_t)(rng() % 5)};
+    const size_t need = chunkft_group_workspace_bytes(sg.data(), n);
+    size_t have = need;
+    if (need > 0 && rng() % 10 == 0) have = need - 1;
+    void* ws = have ? (void*)(base + 0x4000000u) : nullptr;
+    g_ws_lo = reinterpret_cast<uintptr_t>(ws);
+    g_ws_hi = g_ws_lo + have;
+    const long before = g_launches;
+    const int r = chunkft_wgrad_adamw_fused_group(sg.data(), n, &hp, ws, have, nullptr);
+    ++groups;
+    if (r == CHUNKFT_OK) {
+      ++groups_ok;
+      if (g_launches == before) { printf("accepted group launched nothing at %d\n", it); return 1; }
+    } else if (g_launches != before) {
+      printf("rejected group (%d) reached a launcher at %d\n", r, it);
+      return 1;
+    }
+    if (g_fail) { printf("group launch check failed: %s (iteration %d)\n", g_fail, it); return 1; }
+  }
+  if (groups_ok < groups / 4) { printf("too few accepted groups: %ld of %ld\n", groups_ok, groups); return 1; }
   if (accepted < calls / 20) { printf("too few accepted calls: %ld of %ld\n", accepted, calls); return 1; }
-  printf("ok: %ld plans, %ld device calls (%ld accepted, %ld stand-in launches)\n", plans, calls, accepted, g_launches);
+  printf("ok: %ld plans, %ld device calls (%ld accepted), %ld grouped calls (%ld accepted), %ld stand-in launches\n", plans, calls,
+         accepted, groups, groups_ok, g_launches);
   return 0;
 }

@@ -255,11 +255,16 @@ def config4_layers():
 
 
 def _config4_offsets(gate):
-    rng = WL.rng_for(4, 1)
     length = 64 * MiB                                   # 128 MiB of bf16
     # seeded offset in the concatenated [gate | down] space, and one straddling the boundary
-    off = WL.draw_offset(rng, 2 * gate.numel, length, gate.n_in)
-    straddle = gate.numel - length // 3 - 17
+    chunks = WL.config4_chunks(gate.numel, gate.n_in, gate.numel, length)
+
+    def start(segs):
+        t, b, _ = segs[0]
+        return b + (gate.numel if t == 1 else 0)
+
+    off, straddle = start(chunks["seeded"]), start(chunks["straddling"])
+    assert straddle == gate.numel - length // 3 - 17
     return length, off, straddle
 
 

@@ -204,6 +204,18 @@ def test_bf16_many_tiles_take_the_large_tile(T):
     _full_check(case, 4096 * 3 + 77, 4096 * 2397 + 5, check_accum=True)
 
 
+@pytest.mark.parametrize("begin,end", [(10928 * 3 + 40, 10928 * 515 + 9000), (10928 * 8, 10928 * 272)])
+def test_bf16_long_token_count_takes_the_large_tile_in_the_fused_call(begin, end):
+    """Many tokens and a wide layer (T >= 6144 and X of 128 MiB or more) send the fused call to the
+    256 x 256 tile with the AdamW epilogue: whole oracle comparison on a layer of three tile rows
+    (the last of 8 rows) and a ragged last column tile, with and without edge rows, and the
+    bit-identity of the fused call with the un-fused pair."""
+    rng = np.random.default_rng(WL.SEED_BASE + 45)
+    case = WL.linear_case(rng, "long-wide", 520, 10928, 6144, WL.BF16, 1e-3)
+    assert case.T >= 6144 and case.T * case.n_in * 2 >= (128 << 20)
+    _full_check(case, begin, end, check_accum=False)
+
+
 @pytest.mark.parametrize("split_k", [2, 3, 4])
 def test_bf16_forced_token_split(split_k):
     case = _small_bf16(T=200)
@@ -405,28 +417,124 @@ def test_config5_scaled_chunk_sizes():
         _full_check(case, begin, end, check_accum=False)
 
 
-def _run_cycle(layers, budget, flags=0):
-    """One full-parameter cycle on the GPU: plan, then one fused call per segment."""
+def _run_cycle(layers, budget, flags=0, grouped=False, split_k=0):
+    """One full-parameter cycle on the GPU: plan, then one fused call per segment, or (grouped)
+    one chunkft_wgrad_adamw_fused_group call per chunk."""
     tensors = [(c.out, c.n_in, c.dtype, c.kind) for c in layers]
     st, chunks, segs = B.chunkft_plan_cycle(tensors, budget, flags)
-    dls = [H.DeviceLayer(c) for c in layers]
+    dls = [H.DeviceLayer(c, split_k=split_k) for c in layers]
     Wd = [c.W0.reshape(-1).clone().to(H.DEV) for c in layers]
     masters, ms, vs = [], [], []
     for (s0, s1, numel, _) in chunks:
-        master = torch.empty(numel, dtype=torch.float32, device=H.DEV)
+        fm, master = H.guarded(numel)
         for (t, b, e, off) in segs[s0:s1]:
             master[off:off + (e - b)] = Wd[t][b:e].float()
-        m = torch.zeros(numel, dtype=torch.float32, device=H.DEV)
-        v = torch.zeros(numel, dtype=torch.float32, device=H.DEV)
-        for (t, b, e, off) in segs[s0:s1]:
-            layer = dls[t].layer()
-            ws = H.workspace_for(layer, b, e)
-            n = e - b
-            B.chunkft_wgrad_adamw_fused(layer, b, e, Wd[t], master[off:off + n], m[off:off + n],
-                                        v[off:off + n], B.hparams(step=1, **HP), ws=ws)
+        fmm, m = H.guarded(numel, torch.zeros(numel))
+        fv, v = H.guarded(numel, torch.zeros(numel))
+        if grouped:
+            group = B.GroupCall([(dls[t].layer(), b, e, Wd[t], master[off:off + e - b], m[off:off + e - b],
+                                  v[off:off + e - b]) for (t, b, e, off) in segs[s0:s1]], device=H.DEV)
+            group(B.hparams(step=1, **HP))
+        else:
+            for (t, b, e, off) in segs[s0:s1]:
+                layer = dls[t].layer()
+                ws = H.workspace_for(layer, b, e)
+                n = e - b
+                B.chunkft_wgrad_adamw_fused(layer, b, e, Wd[t], master[off:off + n], m[off:off + n],
+                                            v[off:off + n], B.hparams(step=1, **HP), ws=ws)
+        torch.cuda.synchronize()
+        assert H.guards_intact(fm) and H.guards_intact(fmm) and H.guards_intact(fv)
         masters.append(master); ms.append(m); vs.append(v)
-    torch.cuda.synchronize()
     return chunks, segs, Wd, masters, ms, vs
+
+
+@pytest.mark.parametrize("budget_mib_x16,rows8", [(256, False), (100, False), (100, True), (20, False)])
+def test_grouped_call_equals_one_call_per_segment(budget_mib_x16, rows8):
+    """chunkft_wgrad_adamw_fused_group on every chunk of the scaled transformer block (matrix
+    segments with and without edge rows, the two scale vectors, cuts in mid-row) against one
+    chunkft_wgrad_adamw_fused call per segment: master, m, v of every chunk and every tensor's bf16
+    copy bit for bit (the per-segment results are checked against the oracle in
+    test_config3_scaled_cycle)."""
+    layers = WL.config3(scale=4, T=256)
+    budget = budget_mib_x16 * (1 << 20) // 16 + (2 if budget_mib_x16 != 256 else 0)
+    flags = B.PLAN_ROWS8 if rows8 else 0
+    # the 256 MiB plan's chunks fill the device and are grouped as they are; the smaller ones would each be
+    # handed to the single call's own split rule, so one slab is asked for (in both runs) to group them
+    split_k = 0 if budget_mib_x16 == 256 else 1
+    a = _run_cycle(layers, budget, flags, split_k=split_k)
+    b = _run_cycle(layers, budget, flags, grouped=True, split_k=split_k)
+    assert a[0] == b[0] and a[1] == b[1] and len(a[0]) >= 2
+    for k in range(len(a[0])):
+        for x, y, name in ((a[3][k], b[3][k], "master"), (a[4][k], b[4][k], "m"), (a[5][k], b[5][k], "v")):
+            assert torch.equal(x.view(torch.int32), y.view(torch.int32)), f"{name} of chunk {k}"
+    for t in range(len(layers)):
+        assert torch.equal(a[2][t].view(torch.int16), b[2][t].view(torch.int16)), f"W of tensor {t}"
+    for k, (s0, s1, numel, _) in enumerate(a[0]):                 # and the grouped call did update every segment
+        for (t, lo, hi, off) in a[1][s0:s1]:
+            assert not torch.equal(b[3][k][off:off + hi - lo], layers[t].W0.reshape(-1)[lo:hi].float().to(H.DEV))
+
+
+def test_grouped_call_runs_what_its_kernel_cannot_take_by_itself():
+    """A group that mixes segments for the one-launch kernel (bf16 matrices, a bf16 scale vector) with
+    ones it cannot take -- an fp32 matrix, a forced token split, a chunk of three rows, an embedding
+    table, a self-normalising scale vector -- and more than twelve segments in all, so that the table
+    is cut into several launches.  Every segment's state against the single call's, bit for bit."""
+    rng = np.random.default_rng(WL.SEED_BASE + 80)
+    cases = []
+
+    def add(case, begin, end, split_k=0):
+        cases.append((case, begin, end, split_k))
+
+    big = WL.linear_case(rng, "a", 776, 520, 200, WL.BF16, 1e-3)
+    add(big, 520 * 3 + 17, 520 * 400 + 9, 1)                       # edge rows on both sides
+    add(big, 520 * 408, 520 * 776, 1)                              # row aligned, another range of the same tensor
+    add(WL.linear_case(rng, "b", 264, 136, 200, WL.F32, 1e-3), 77, 136 * 200 + 3)      # fp32: by itself
+    add(WL.linear_case(rng, "c", 520, 264, 200, WL.BF16, 1e-3), 264 * 5 + 1, 264 * 519 + 100, 3)   # forced split
+    add(WL.linear_case(rng, "d", 520, 264, 200, WL.BF16, 1e-3), 264 * 10 + 7, 264 * 13 + 5)        # three rows
+    add(WL.vector_case(rng, "e", 1032, 200, WL.BF16, 1e-3), 5, 1000)
+    add(WL.embedding_case(rng, "f", 300, 264, 150, WL.BF16, 1e-3), 264 * 3 + 9, 264 * 290)
+    add(WL.norm_case(rng, "g", 520, 200, WL.BF16, 1e-3, WL.RMSNORM), 0, 520)
+    for i in range(8):                                             # fills the table past twelve segments
+        c = WL.linear_case(rng, f"h{i}", 264 + 8 * i, 136, 200, WL.BF16, 1e-3)
+        add(c, 136 * i + i, 136 * (200 + i) + 3 * i, 1)             # one slab asked for: the kernel takes them
+    assert len(cases) == 16
+    hp = B.hparams(step=2, **HP)
+
+    def run(grouped):
+        out, keep, segs = [], [], []
+        for case, begin, end, split_k in cases:
+            dl = H.DeviceLayer(case, split_k=split_k)
+            layer = dl.layer()
+            n = end - begin
+            is_bf16 = case.dtype == WL.BF16
+            W = case.W0.reshape(-1).clone().to(H.DEV)
+            th0, m0, v0 = _state_for(case, begin, end, np.random.default_rng(7), warm=True)
+            st = [H.guarded(n, torch.from_numpy(x)) for x in (th0, m0, v0)]
+            keep.append((dl, layer, W, st))
+            segs.append((layer, begin, end, W if is_bf16 else None, st[0][1], st[1][1], st[2][1]))
+        if grouped:
+            call = B.GroupCall(segs, device=H.DEV)
+            assert call.ws_bytes > 0                                # the forced split and the norm need some
+            call(hp)
+        else:
+            for (layer, begin, end, W, master, m, v) in segs:
+                ws = H.workspace_for(layer, begin, end)
+                B.chunkft_wgrad_adamw_fused(layer, begin, end, W, master, m, v, hp, ws=ws)
+                torch.cuda.synchronize()
+                assert H.workspace_intact(ws)
+        torch.cuda.synchronize()
+        for (dl, layer, W, st) in keep:
+            assert all(H.guards_intact(f) for f, _ in st)
+            out.append((W.cpu(), [x.cpu() for _, x in st]))
+        return out
+
+    single, grouped = run(False), run(True)
+    for i, ((Wa, sa), (Wb, sb)) in enumerate(zip(single, grouped)):
+        for x, y in zip(sa, sb):
+            assert torch.equal(x.view(torch.int32), y.view(torch.int32)), f"state of segment {i}"
+        assert torch.equal(Wa.view(torch.uint8), Wb.view(torch.uint8)), f"W of segment {i}"
+        assert not torch.equal(sa[0], torch.from_numpy(_state_for(cases[i][0], cases[i][1], cases[i][2],
+                                                                  np.random.default_rng(7), warm=True)[0]))
 
 
 @pytest.mark.parametrize("budget_mib_x16,rows8", [(256, False), (64, False), (100, False), (100, True)])

@@ -311,6 +311,50 @@ def test_device_calls_reject_bad_arguments_without_launching():
     assert lib.chunkft_adamw_chunk(P, P, P, P, P + 1, B.BF16, 10, C.byref(hp), None) == B.ERR_INVALID_ARG
 
 
+def test_grouped_call_rejects_bad_arguments_without_launching():
+    lib = B.lib()
+    hp = B.hparams(1e-4, 0.9, 0.999, 1e-8, 0.01, 1)
+
+    def seg(layer, b, e, W=P, master=P, m=P, v=P):
+        return B.GroupSegment(layer, b, e, W, master, m, v)
+
+    good = seg(_layer(), 0, 100)
+    cases = [
+        ([seg(_layer(T=0), 0, 10)], B.ERR_INVALID_ARG),
+        ([good, seg(_layer(dtype=7), 0, 10)], B.ERR_DTYPE),
+        ([good, seg(_layer(), 10, 10)], B.ERR_RANGE),
+        ([good, seg(_layer(), 0, 10, master=None)], B.ERR_INVALID_ARG),
+        ([good, seg(_layer(), 0, 10, m=P + 2)], B.ERR_INVALID_ARG),
+        ([seg(_layer(T=64, split_k=2), 0, 100)], B.ERR_WORKSPACE),         # a forced split needs a workspace
+        ([seg(_layer(kind=B.RMSNORM, out=1, lddy=32, norm_eps=1e-6), 0, 32)], B.ERR_WORKSPACE),
+    ]
+    for segs, want in cases:
+        arr = (B.GroupSegment * len(segs))(*segs)
+        assert lib.chunkft_wgrad_adamw_fused_group(arr, len(segs), C.byref(hp), None, 0, None) == want
+    arr = (B.GroupSegment * 1)(good)
+    assert lib.chunkft_wgrad_adamw_fused_group(None, 1, C.byref(hp), None, 0, None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_wgrad_adamw_fused_group(arr, 0, C.byref(hp), None, 0, None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_wgrad_adamw_fused_group(arr, 4097, C.byref(hp), None, 0, None) == B.ERR_INVALID_ARG
+    assert lib.chunkft_wgrad_adamw_fused_group(arr, 1, None, None, 0, None) == B.ERR_INVALID_ARG
+    bad = B.hparams(1e-4, 0.9, 0.999, 1e-8, 0.01, 0)
+    assert lib.chunkft_wgrad_adamw_fused_group(arr, 1, C.byref(bad), None, 0, None) == B.ERR_INVALID_ARG
+    # workspace: the largest need among the segments that run by themselves; none when the kernel takes all
+    forced = seg(_layer(T=64, split_k=2), 0, 100)
+    norm = seg(_layer(kind=B.RMSNORM, out=1, lddy=32, norm_eps=1e-6), 0, 32)
+    assert lib.chunkft_group_workspace_bytes((B.GroupSegment * 1)(forced), 1) == (2 * 128 + 32) * 4
+    assert lib.chunkft_group_workspace_bytes((B.GroupSegment * 2)(forced, norm), 2) == (2 * 128 + 32) * 4
+    assert lib.chunkft_group_workspace_bytes((B.GroupSegment * 1)(norm), 1) == 16 * 8
+    big = _layer(out=14336, n_in=4096, T=1024, ldx=4096, lddy=14336)
+    vec = _layer(kind=B.VECTOR, out=1, n_in=4096, T=1024, ldx=4096, lddy=4096)
+    kv = _layer(out=1024, n_in=4096, T=8192, ldx=4096, lddy=1024)
+    whole = (B.GroupSegment * 3)(seg(big, 4097, 4097 + (32 << 20)), seg(vec, 0, 4096), seg(kv, 0, 1024 * 4096))
+    assert lib.chunkft_group_workspace_bytes(whole, 3) == 0
+    # by itself the k projection at 8192 tokens is split into three slabs and needs their workspace
+    alone = (B.GroupSegment * 1)(seg(kv, 0, 1024 * 4096))
+    assert lib.chunkft_group_workspace_bytes(alone, 1) == (3 * 1024 * 4096 + 32) * 4
+    assert lib.chunkft_group_workspace_bytes(None, 1) == 0
+
+
 def test_split_is_a_pure_function_of_shape():
     lib = B.lib()
     # 8B up_proj chunk: many tiles, no split
