@@ -1518,9 +1518,16 @@ int launch_wgrad_bf16_mfma(const WgradProblem& p, int mode, const Sinks& s, void
   }
   // A segment whose large tiles would occupy at most half the compute units takes the small
   // tile too: twice the workgroups, each element still summed over the tokens in the same order.
+  // So does a call with few tokens per slab: its loops are short, and two workgroups per compute unit,
+  // which drift apart, spread the bursts of stores that one workgroup per compute unit sends out in
+  // step (measured on 32 Mi elements of 14336 x 4096: 77 - 81 against 79 - 84 us at 1024 tokens, 122 - 128
+  // against 123 - 133 us at 2048, on 4096 x 14336 88 against 100 us; from 4096 tokens on the large tile's
+  // third less operand traffic wins, 212 against 220 us).
   const RowSplit rs = split_rows(p);
   const int64_t big_tiles = ceil_div(rs.rb1 - rs.rb0, MainCfg::BM) * ceil_div(p.in, MainCfg::BN) * p.S;
-  if (big_tiles <= device_compute_units() / 2) return launch_mfma_cfg<FusedCfg>(p, mode, s, (hipStream_t)stream);
+  const int64_t slab_tokens = p.S > 1 ? p.kslab : p.T;
+  if (big_tiles <= device_compute_units() / 2 || slab_tokens <= 2048)
+    return launch_mfma_cfg<FusedCfg>(p, mode, s, (hipStream_t)stream);
   return launch_mfma_cfg<MainCfg>(p, mode, s, (hipStream_t)stream);
 }
 

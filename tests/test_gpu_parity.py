@@ -195,10 +195,11 @@ def test_bf16_ranges_with_chunk_arrays_at_the_tensor_phase(begin, end):
         _full_check(_small_bf16(n_in=288), begin, end)
 
 
-@pytest.mark.parametrize("T", [70, 96, 161])
-def test_bf16_many_tiles_take_the_large_tile(T):
-    """More than 128 tiles of 256 x 256: the plain gradient runs on the large tile, here with token
-    counts that leave a ragged last slab (70, 161) or none (96), and a range with edge rows."""
+@pytest.mark.parametrize("T", [70, 96, 161, 2070, 2080])
+def test_bf16_many_tiles_at_short_and_long_token_counts(T):
+    """More than 128 tiles of 256 x 256 and a range with edge rows.  Up to 2048 tokens the plain gradient
+    runs on the small tile (two workgroups per compute unit), beyond on the large one; token counts
+    that leave a ragged last slab (70, 161, 2070) or none (96, 2080)."""
     rng = np.random.default_rng([83, T])
     case = WL.linear_case(rng, "many tiles", 2400, 4096, T, WL.BF16, 1e-3)
     _full_check(case, 4096 * 3 + 77, 4096 * 2397 + 5, check_accum=True)
