@@ -61,6 +61,11 @@ def main():
     ap.add_argument("--no-per-config", action="store_true",
                     help="skip the \"per_config\" block (every other configuration of the task's list timed on "
                          "device-generated operands of its shapes, a few milliseconds each)")
+    ap.add_argument("--timeline", action="store_true",
+                    help="instead of the benchmark: run the plain gradient of the workload once more through "
+                         "libchunkft_timeline.so (the library built with the MFMA kernel's time stamps) and print "
+                         "where each workgroup's time goes: start, first fragments in registers, end of loop, "
+                         "end of epilogue, per compute unit")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region, run a plain device copy of known size (256 MiB read, "
                          "256 MiB written, three times): the calibration point for rocprofv3 --pmc "
@@ -133,6 +138,10 @@ def main():
             marks[3].record()
             for k, n in enumerate(names):
                 ev[n].append((marks[k], marks[k + 1]))
+
+    if args.timeline:
+        print(json.dumps(timeline(torch, np, B, dev, layer, begin, end, g, ws, T)), flush=True)
+        return
 
     for i in range(args.warmup):
         step(i, False)
@@ -255,6 +264,70 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(case, begin, end, hp)
     print(json.dumps(out), flush=True)
+
+
+def timeline(torch, np, B, dev, layer, begin, end, g, ws, T):
+    """Phase times of every workgroup of the plain gradient's MFMA kernel at the benchmark workload, from
+    the diagnostic build of the library.  Times are the 100 MHz constant counter (10 ns steps)."""
+    L = B.load_timeline_library()
+    cap = 1 << 16
+    buf = torch.zeros(cap * 8, dtype=torch.int64, device=dev)
+    with B.use_library(L):
+        for _ in range(3):
+            B.chunkft_chunk_wgrad(layer, begin, end, g, ws=ws)
+        torch.cuda.synchronize()
+        L.chunkft_timeline_buffer(buf.data_ptr(), buf.numel() * 8)
+        B.chunkft_chunk_wgrad(layer, begin, end, g, ws=ws)
+        torch.cuda.synchronize()
+        L.chunkft_timeline_buffer(None, 0)
+    t = buf.cpu().numpy().reshape(cap, 8)
+    t = t[t[:, 0] != 0]
+    us = lambda ticks: ticks / 100.0
+    t0 = t[:, 0].min()
+    start, frag, loop_end, done = (us(t[:, k] - t0) for k in range(4))
+    where = t[:, 4]
+    hw = where & 0xffffffff
+    # HW_ID: compute unit [11:8], shader array [12], shader engine [15:13]; XCC_ID [3:0] in the upper word
+    cu = ((where >> 32) & 0xf) * 4096 + ((hw >> 13) & 7) * 64 + ((hw >> 12) & 1) * 16 + ((hw >> 8) & 0xf)
+    span = float(done.max())
+    units = np.unique(cu)
+
+    def stats(x):
+        return {"mean": round(float(x.mean()), 2), "p10": round(float(np.quantile(x, 0.1)), 2),
+                "median": round(float(np.median(x)), 2), "p90": round(float(np.quantile(x, 0.9)), 2)}
+
+    # per compute unit: how long at least one / two of its workgroups are in their MFMA loop
+    one_loop, two_loops, first_start, last_done, per_cu = [], [], [], [], []
+    for u in units:
+        sel = cu == u
+        ev = sorted([(a, 1) for a in frag[sel]] + [(b, -1) for b in loop_end[sel]])
+        depth, prev, t1, t2 = 0, 0.0, 0.0, 0.0
+        for when, d in ev:
+            if depth >= 1: t1 += when - prev
+            if depth >= 2: t2 += when - prev
+            depth += d
+            prev = when
+        one_loop.append(t1); two_loops.append(t2)
+        first_start.append(start[sel].min()); last_done.append(done[sel].max()); per_cu.append(int(sel.sum()))
+    one_loop, two_loops = np.array(one_loop), np.array(two_loops)
+    order = np.argsort(start)
+    rounds = {}
+    n_first = len(units) * (2 if len(t) >= 2 * len(units) else 1)
+    for name, sel in (("workgroups started first on their place", order[:n_first]), ("workgroups started later", order[n_first:])):
+        if len(sel):
+            rounds[name] = {"count": int(len(sel)), "start_us": stats(start[sel]),
+                            "first_fragments_after_us": stats((frag - start)[sel]),
+                            "loop_us": stats((loop_end - frag)[sel]), "epilogue_us": stats((done - loop_end)[sel])}
+    return {"kernel": "wgrad_mfma_kernel, plain gradient of the benchmark workload (libchunkft_timeline.so)",
+            "workgroups": int(len(t)), "compute_units_seen": int(len(units)), "workgroups_per_compute_unit": stats(np.array(per_cu)),
+            "span_us": round(span, 2),
+            "phase_us_per_workgroup": {"first_fragments_after_start": stats(frag - start), "loop": stats(loop_end - frag),
+                                       "epilogue": stats(done - loop_end), "whole": stats(done - start)},
+            "by_round": rounds,
+            "per_compute_unit_us": {"first_start": stats(np.array(first_start)), "last_end": stats(np.array(last_done)),
+                                    "some_workgroup_in_its_loop": stats(one_loop), "two_workgroups_in_their_loops": stats(two_loops),
+                                    "no_workgroup_in_its_loop": stats(span - one_loop)},
+            "mfma_flops_time_at_2.5_PFLOPs_us": round(2.0 * T * (end - begin) / 2.5e15 * 1e6, 2)}
 
 
 def llama3_8b_tensors(B):

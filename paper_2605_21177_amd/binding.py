@@ -89,17 +89,49 @@ class ChunkFTError(RuntimeError):
 
 
 _lib = None
+TIMELINE_LIB_PATH = os.path.join(_HERE, "libchunkft_timeline.so")
 
 
 def lib() -> C.CDLL:
     """The loaded library; raises if it has not been built."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
+        _lib = _load(LIB_PATH)
+    return _lib
+
+
+class use_library:
+    """with use_library(handle): the calls of this module go to another build of the library (the
+    diagnostic twin that bench.py --timeline loads)."""
+
+    def __init__(self, handle):
+        self.handle = handle
+
+    def __enter__(self):
+        global _lib
+        self.prev, _lib = _lib, self.handle
+        return self.handle
+
+    def __exit__(self, *exc):
+        global _lib
+        _lib = self.prev
+
+
+def load_timeline_library() -> C.CDLL:
+    """libchunkft_timeline.so: the same sources with the MFMA kernel's phase time stamps compiled in."""
+    L = _load(TIMELINE_LIB_PATH)
+    L.chunkft_timeline_buffer.restype = C.c_int
+    L.chunkft_timeline_buffer.argtypes = [C.c_void_p, C.c_size_t]
+    return L
+
+
+def _load(path) -> C.CDLL:
+    if True:
+        if not os.path.exists(path):
             raise FileNotFoundError(
-                f"{LIB_PATH} is missing: build it with `python -m paper_2605_21177_amd.build` "
+                f"{path} is missing: build it with `python -m paper_2605_21177_amd.build` "
                 "(there is no fallback path)")
-        L = C.CDLL(LIB_PATH)
+        L = C.CDLL(path)
         L.chunkft_plan_cycle.restype = C.c_int
         L.chunkft_plan_cycle.argtypes = [C.POINTER(TensorDesc), C.c_int32, C.c_int64, C.c_uint32,
                                          C.POINTER(Chunk), C.c_int64, C.POINTER(C.c_int64),
@@ -154,8 +186,7 @@ def lib() -> C.CDLL:
         L.chunkft_calib_mfma_bf16.restype = C.c_int
         L.chunkft_calib_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.POINTER(C.c_double),
                                               C.POINTER(C.c_double), C.c_void_p]
-        _lib = L
-    return _lib
+    return L
 
 
 EXPORTS = ("chunkft_plan_cycle", "chunkft_plan_stats", "chunkft_split_k", "chunkft_workspace_bytes", "chunkft_chunk_wgrad",

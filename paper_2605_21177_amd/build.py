@@ -18,6 +18,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libchunkft.so")
+LIB_TIMELINE = os.path.join(PKG, "libchunkft_timeline.so")   # diagnostic twin: workgroups note their phase times
 
 SOURCES = ["kernels.hip", "static_ws.hip", "calib.hip", "api.cpp", "shape.cpp", "plan.cpp", "mover.cpp"]
 
@@ -49,24 +50,34 @@ def _headers():
     return hs
 
 
-def build_library(verbose: bool = False, only_changed: bool = False) -> str:
+def build_library(verbose: bool = False, only_changed: bool = False, timeline: bool = True) -> str:
+    """libchunkft.so, and with `timeline` also libchunkft_timeline.so (kernels.hip built once more with
+    -DCHUNKFT_TIMELINE; the other objects are shared)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ, exist_ok=True)
     newest_header = max(os.path.getmtime(h) for h in _headers())
     jobs = []
     objs = []
+
+    def want(src, obj, extra=()):
+        fresh = os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header)
+        if not (only_changed and fresh):
+            jobs.append([hipcc] + FLAGS + list(extra) + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", src, "-o", obj])
+
     for s in SOURCES:
-        src = os.path.join(CSRC, s)
         obj = os.path.join(OBJ, os.path.splitext(s)[0] + ".o")
         objs.append(obj)
-        fresh = os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header)
-        if only_changed and fresh:
-            continue
-        jobs.append([hipcc] + FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", src, "-o", obj])
+        want(os.path.join(CSRC, s), obj)
+    tl_obj = os.path.join(OBJ, "kernels_timeline.o")
+    if timeline:
+        want(os.path.join(CSRC, "kernels.hip"), tl_obj, ["-DCHUNKFT_TIMELINE"])
     workers = max(1, min(len(jobs), os.cpu_count() or 1, 16))
     with ThreadPoolExecutor(max_workers=workers) as pool:
         list(pool.map(lambda c: _run(c, verbose), jobs))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB], verbose)
+    if timeline:
+        tl_objs = [tl_obj if o.endswith(os.sep + "kernels.o") else o for o in objs]
+        _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + tl_objs + ["-o", LIB_TIMELINE], verbose)
     return LIB
 
 

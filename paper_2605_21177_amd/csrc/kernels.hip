@@ -182,6 +182,27 @@ __device__ __forceinline__ void finish4(const Vec4Sink& d, int w_kind, const Ada
 //   first tile row, which stream every X column tile anyway, carry them as one
 //   extra 32-row MFMA block; only when the body has at most 128 rows (a chunk of a
 //   few rows) does the small FMA edge kernel compute them.
+// Diagnostic build only (-DCHUNKFT_TIMELINE, a library of its own: libchunkft_timeline.so): every
+// workgroup of the MFMA kernel notes when it starts, when the first fragments of its tile are in
+// registers, when its loop ends and when its epilogue ends (the 100 MHz constant counter), and where
+// it ran, in 8 words per work item of a buffer that the caller hands over with
+// chunkft_timeline_buffer().  The product library has none of this.
+#ifdef CHUNKFT_TIMELINE
+static unsigned long long* g_timeline = nullptr;
+static size_t g_timeline_words = 0;
+extern "C" int chunkft_timeline_buffer(void* device_buffer, size_t bytes) {
+  g_timeline = static_cast<unsigned long long*>(device_buffer);
+  g_timeline_words = bytes / 8;
+  return 0;
+}
+#define TIMELINE_STAMP(q, item, k)                                                                  \
+  do {                                                                                              \
+    if ((q).timeline && threadIdx.x == 0) (q).timeline[(size_t)(item) * 8 + (k)] = __builtin_amdgcn_s_memrealtime(); \
+  } while (0)
+#else
+#define TIMELINE_STAMP(q, item, k) do { } while (0)
+#endif
+
 struct MfmaParams {
   WgradProblem p;
   int64_t rb0, rb1;
@@ -192,6 +213,9 @@ struct MfmaParams {
   int64_t lead_base;           // edge rows folded into the first tile row (-1: none), as in EdgeParams
   int64_t trail_row;
   Sinks s;
+#ifdef CHUNKFT_TIMELINE
+  unsigned long long* timeline;
+#endif
 };
 
 struct EdgeParams {
@@ -480,6 +504,13 @@ __device__ __forceinline__ void tile_epilogue(const MfmaParams& q, unsigned char
 template <class C, int MODE>
 __device__ __forceinline__ void mfma_tile(const MfmaParams& q, const int item, unsigned char* ldsb) {
   const WgradProblem& p = q.p;
+  TIMELINE_STAMP(q, item, 0);
+#ifdef CHUNKFT_TIMELINE
+  // where: XCC_ID (hardware register 20) and HW_ID (4: wave, SIMD, compute unit, shader engine)
+  if (q.timeline && threadIdx.x == 0)
+    q.timeline[(size_t)item * 8 + 4] = ((unsigned long long)__builtin_amdgcn_s_getreg((32 - 1) << 11 | 20) << 32) |
+                                       (unsigned)__builtin_amdgcn_s_getreg((32 - 1) << 11 | 4);
+#endif
 
   // ---- which tile, which token slab
   const int n_tiles = q.tiles_m * q.tiles_n;
@@ -733,6 +764,7 @@ __device__ __forceinline__ void mfma_tile(const MfmaParams& q, const int item, u
   if (has_edge) read_edge(he0, 0u, IntC<0>{});
   WAIT_HALVES_E(h0, he0);
   mask_halves(h0, he0, 0, 0);
+  TIMELINE_STAMP(q, item, 1);
 
   // One slab: sixteen MFMAs in two steps of eight, numbered i = 2a + b within a
   // step.  The twelve transpose reads of the next step follow MFMAs 0-2 (four
@@ -830,8 +862,10 @@ __device__ __forceinline__ void mfma_tile(const MfmaParams& q, const int item, u
     for (; kt < nk; ++kt) do_slab(kt, IntC<-1>{}, edgec);
   };
   if (has_edge) run_slabs(IntC<1>{}); else run_slabs(IntC<0>{});
+  TIMELINE_STAMP(q, item, 2);
 
   tile_epilogue<C, MODE>(q, ldsb, row0, col0, slab, wave, lane, tid, acc, has_edge, edge_blk, acc_e);
+  TIMELINE_STAMP(q, item, 3);
 }
 
 // Workgroup ids are dealt round-robin to the 8 XCDs; each XCD gets one contiguous run of work
@@ -1420,6 +1454,9 @@ int launch_mfma_mode(const MfmaParams& q, int grid, hipStream_t st) {
   }
   MfmaArgs args;
   args.q[0] = q;
+#ifdef CHUNKFT_TIMELINE
+  args.q[0].timeline = g_timeline_words >= (size_t)q.n_tile_items * 8 ? g_timeline : nullptr;
+#endif
   hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS_BYTES, st, args);
   return (int)hipGetLastError();
 }
