@@ -61,8 +61,8 @@ def main():
     ap.add_argument("--no-per-config", action="store_true",
                     help="skip the \"per_config\" block (every other configuration of the task's list timed on "
                          "device-generated operands of its shapes, a few milliseconds each)")
-    ap.add_argument("--timeline", action="store_true",
-                    help="instead of the benchmark: run the plain gradient of the workload once more through "
+    ap.add_argument("--timeline", nargs="?", const="wgrad", choices=("wgrad", "fused"),
+                    help="instead of the benchmark: run the plain gradient (or, with `fused`, the fused call) of the workload through "
                          "libchunkft_timeline.so (the library built with the MFMA kernel's time stamps) and print "
                          "where each workgroup's time goes: start, first fragments in registers, end of loop, "
                          "end of epilogue, per compute unit")
@@ -140,7 +140,8 @@ def main():
                 ev[n].append((marks[k], marks[k + 1]))
 
     if args.timeline:
-        print(json.dumps(timeline(torch, np, B, dev, layer, begin, end, g, ws, T)), flush=True)
+        print(json.dumps(timeline(torch, np, B, dev, layer, begin, end, g, ws, T,
+                                  fused=(Wb, stB, B.hparams(step=1, **hp)) if args.timeline == "fused" else None)), flush=True)
         return
 
     for i in range(args.warmup):
@@ -266,18 +267,25 @@ def main():
     print(json.dumps(out), flush=True)
 
 
-def timeline(torch, np, B, dev, layer, begin, end, g, ws, T):
+def timeline(torch, np, B, dev, layer, begin, end, g, ws, T, fused=None):
     """Phase times of every workgroup of the plain gradient's MFMA kernel at the benchmark workload, from
     the diagnostic build of the library.  Times are the 100 MHz constant counter (10 ns steps)."""
     L = B.load_timeline_library()
     cap = 1 << 16
     buf = torch.zeros(cap * 8, dtype=torch.int64, device=dev)
+    def call():
+        if fused is None:
+            B.chunkft_chunk_wgrad(layer, begin, end, g, ws=ws)
+        else:
+            W, st, h = fused
+            B.chunkft_wgrad_adamw_fused(layer, begin, end, W, st[0], st[1], st[2], h, ws=ws)
+
     with B.use_library(L):
         for _ in range(3):
-            B.chunkft_chunk_wgrad(layer, begin, end, g, ws=ws)
+            call()
         torch.cuda.synchronize()
         L.chunkft_timeline_buffer(buf.data_ptr(), buf.numel() * 8)
-        B.chunkft_chunk_wgrad(layer, begin, end, g, ws=ws)
+        call()
         torch.cuda.synchronize()
         L.chunkft_timeline_buffer(None, 0)
     t = buf.cpu().numpy().reshape(cap, 8)
@@ -318,7 +326,8 @@ def timeline(torch, np, B, dev, layer, begin, end, g, ws, T):
             rounds[name] = {"count": int(len(sel)), "start_us": stats(start[sel]),
                             "first_fragments_after_us": stats((frag - start)[sel]),
                             "loop_us": stats((loop_end - frag)[sel]), "epilogue_us": stats((done - loop_end)[sel])}
-    return {"kernel": "wgrad_mfma_kernel, plain gradient of the benchmark workload (libchunkft_timeline.so)",
+    return {"kernel": "wgrad_mfma_kernel, %s of the benchmark workload (libchunkft_timeline.so)" % (
+                "plain gradient" if fused is None else "fused call"),
             "workgroups": int(len(t)), "compute_units_seen": int(len(units)), "workgroups_per_compute_unit": stats(np.array(per_cu)),
             "span_us": round(span, 2),
             "phase_us_per_workgroup": {"first_fragments_after_start": stats(frag - start), "loop": stats(loop_end - frag),
