@@ -245,6 +245,55 @@ def test_config3_full_size_cycle():
             assert H.rel_frobenius(g.cpu().numpy(), ref) <= 3e-3
 
 
+def test_config3_full_size_cycle_in_one_launch_per_chunk():
+    """The transformer block at full size in the benchmark's launch shape: each of the planner's two chunks
+    (6 and 4 segments, 4096 and 2688 work items) through chunkft_wgrad_adamw_fused_group, with the chunk's state in
+    one set of arrays cut at the planner's chunk_off.  Every segment's state and every tensor's bf16 copy must equal,
+    bit for bit, what one chunkft_wgrad_adamw_fused call per segment gives (whose values the test above holds
+    against the oracle); nothing outside the chunks' state arrays is written."""
+    layers = WL.config3()
+    tensors = [(c.out, c.n_in, c.dtype, c.kind) for c in layers]
+    st, chunks, segs = B.chunkft_plan_cycle(tensors, 256 * MiB)
+    dls = [H.DeviceLayer(c) for c in layers]
+    hp = B.hparams(step=1, **HP)
+    results = []
+    for grouped in (False, True):
+        Wd = [c.W0.reshape(-1).clone().to(H.DEV) for c in layers]
+        states = []
+        for (s0, s1, numel, _) in chunks:
+            fm, master = H.guarded(numel)
+            for (t, b, e, off) in segs[s0:s1]:
+                master[off:off + (e - b)] = Wd[t][b:e].float()
+            fmm, m = H.guarded(numel, torch.zeros(1).expand(numel))
+            fv, v = H.guarded(numel, torch.zeros(1).expand(numel))
+            if grouped:
+                call = B.GroupCall([(dls[t].layer(), b, e, Wd[t], master[off:off + e - b], m[off:off + e - b],
+                                     v[off:off + e - b]) for (t, b, e, off) in segs[s0:s1]], device=H.DEV)
+                assert call.ws_bytes == 0                  # the kernel takes every segment of these chunks
+                call(hp)
+            else:
+                for (t, b, e, off) in segs[s0:s1]:
+                    n = e - b
+                    B.chunkft_wgrad_adamw_fused(dls[t].layer(), b, e, Wd[t], master[off:off + n], m[off:off + n],
+                                                v[off:off + n], hp)
+            torch.cuda.synchronize()
+            assert H.guards_intact(fm) and H.guards_intact(fmm) and H.guards_intact(fv)
+            states.append((master, m, v))
+        results.append((Wd, states))
+    (Wa, sa), (Wb, sb) = results
+    for k in range(len(chunks)):
+        for x, y, name in zip(sa[k], sb[k], ("master", "m", "v")):
+            assert torch.equal(x.view(torch.int32), y.view(torch.int32)), f"{name} of chunk {k}"
+            del x, y
+    for t in range(len(layers)):
+        assert torch.equal(Wa[t].view(torch.int16), Wb[t].view(torch.int16)), f"W of tensor {t}"
+    # every master value moved: one update per element of the block
+    for k, (s0, s1, numel, _) in enumerate(chunks):
+        for (t, b, e, off) in segs[s0:s1]:
+            assert not bool((sb[k][0][off:off + e - b] == layers[t].W0.reshape(-1)[b:e].float().to(H.DEV)).any().item()) \
+                or layers[t].kind == WL.VECTOR
+
+
 # ------------------------------------------------------------ configuration 4
 @pytest.fixture(scope="module")
 def config4_layers():
