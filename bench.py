@@ -177,6 +177,26 @@ def main():
 
     flops = 2.0 * T * E
     R = (end - 1) // case.n_in - begin // case.n_in + 1
+
+    # yardstick, not part of the path: the vendor library's GEMM (torch.mm) on the same operands,
+    # the dY columns of the chunk's rows transposed times X, with a bf16 result (half the store traffic)
+    r_first = begin // case.n_in
+
+    def lib_gemm_ms(A):
+        pairs = []
+        for i in range(25):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            torch.mm(A.t(), X)
+            b.record()
+            if i >= 5:
+                pairs.append((a, b))
+        torch.cuda.synchronize()
+        return float(np.median([a.elapsed_time(b) for a, b in pairs]))
+
+    lib_view_ms = lib_gemm_ms(dY[:, r_first:r_first + R])                  # the chunk's own row span, as it lies in dY
+    R_even = E // case.n_in
+    lib_copy_ms = lib_gemm_ms(dY[:, r_first:r_first + R_even].contiguous())  # E / in whole rows, packed
     wgrad_bytes = 2.0 * T * case.n_in + 2.0 * T * R + 4.0 * E        # X once, dY columns once, g once
     adamw_bytes = 30.0 * E                                            # g 4 + state 24 + bf16 W 2
     fused_bytes = 26.0 * E + 2.0 * T * (case.n_in + R)
@@ -221,6 +241,13 @@ def main():
                      "achieved": round(wgrad_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(wgrad_tflops / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC["wgrad"],
                      "algorithmic_bytes": wgrad_bytes,
+                     "library_gemm": {
+                         "what": "yardstick only, not part of the path: torch.mm (the vendor library's GEMM) of the "
+                                 "transposed dY columns with X, bf16 result instead of fp32, median of 20",
+                         "chunk_rows_as_they_lie": {"rows": R, "ms": round(lib_view_ms, 4),
+                                                    "tflops": round(2.0 * T * R * case.n_in / (lib_view_ms * 1e-3) / 1e12, 2)},
+                         "whole_rows_packed": {"rows": R_even, "ms": round(lib_copy_ms, 4),
+                                               "tflops": round(2.0 * T * R_even * case.n_in / (lib_copy_ms * 1e-3) / 1e12, 2)}},
                      "mfma_only_measured": {
                          "what": "32x32x16 bf16 MFMAs issued from registers, nothing else, two waves per SIMD "
                                  "(chunkft_calib_mfma_bf16): the sustained clock, hence the reachable rate, "
