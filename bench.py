@@ -194,6 +194,22 @@ def main():
         torch.cuda.synchronize()
         return float(np.median([a.elapsed_time(b) for a, b in pairs]))
 
+    def pair_floor_us(fn):
+        pairs = []
+        for i in range(60):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            if i >= 10:
+                pairs.append((a, b))
+        torch.cuda.synchronize()
+        return float(np.median([a.elapsed_time(b) for a, b in pairs])) * 1e3
+
+    tiny = torch.zeros(64, device=dev)
+    floor_empty_us = pair_floor_us(lambda: None)
+    floor_tiny_us = pair_floor_us(lambda: tiny.add_(1.0))
+
     lib_view_ms = lib_gemm_ms(dY[:, r_first:r_first + R])                  # the chunk's own row span, as it lies in dY
     R_even = E // case.n_in
     lib_copy_ms = lib_gemm_ms(dY[:, r_first:r_first + R_even].contiguous())  # E / in whole rows, packed
@@ -241,6 +257,9 @@ def main():
                      "achieved": round(wgrad_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(wgrad_tflops / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC["wgrad"],
                      "algorithmic_bytes": wgrad_bytes,
+                     "event_pair_floor_us": {"what": "what the same pair of events reads around nothing and around "
+                                                     "a 64-element kernel: part of every figure here",
+                                             "nothing": round(floor_empty_us, 2), "tiny_kernel": round(floor_tiny_us, 2)},
                      "library_gemm": {
                          "what": "yardstick only, not part of the path: torch.mm (the vendor library's GEMM) of the "
                                  "transposed dY columns with X, bf16 result instead of fp32, median of 20",

@@ -126,66 +126,65 @@ def load_timeline_library() -> C.CDLL:
 
 
 def _load(path) -> C.CDLL:
-    if True:
-        if not os.path.exists(path):
-            raise FileNotFoundError(
-                f"{path} is missing: build it with `python -m paper_2605_21177_amd.build` "
-                "(there is no fallback path)")
-        L = C.CDLL(path)
-        L.chunkft_plan_cycle.restype = C.c_int
-        L.chunkft_plan_cycle.argtypes = [C.POINTER(TensorDesc), C.c_int32, C.c_int64, C.c_uint32,
-                                         C.POINTER(Chunk), C.c_int64, C.POINTER(C.c_int64),
-                                         C.POINTER(Segment), C.c_int64, C.POINTER(C.c_int64)]
-        L.chunkft_plan_stats.restype = C.c_int
-        L.chunkft_plan_stats.argtypes = [C.POINTER(Chunk), C.c_int64, C.c_int64, C.POINTER(PlanSummary)]
-        L.chunkft_split_k.restype = C.c_int
-        L.chunkft_split_k.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64]
-        L.chunkft_workspace_bytes.restype = C.c_size_t
-        L.chunkft_workspace_bytes.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64]
-        L.chunkft_chunk_wgrad.restype = C.c_int
-        L.chunkft_chunk_wgrad.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64, C.c_void_p, C.c_int,
-                                          C.c_void_p, C.c_size_t, C.c_void_p]
-        L.chunkft_adamw_chunk.restype = C.c_int
-        L.chunkft_adamw_chunk.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                                          C.c_int32, C.c_int64, C.POINTER(AdamWHparams), C.c_void_p]
-        L.chunkft_wgrad_adamw_fused.restype = C.c_int
-        L.chunkft_wgrad_adamw_fused.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64, C.c_void_p,
-                                                C.c_void_p, C.c_void_p, C.c_void_p,
-                                                C.POINTER(AdamWHparams), C.c_void_p, C.c_size_t,
-                                                C.c_void_p]
-        L.chunkft_group_workspace_bytes.restype = C.c_size_t
-        L.chunkft_group_workspace_bytes.argtypes = [C.POINTER(GroupSegment), C.c_int32]
-        L.chunkft_wgrad_adamw_fused_group.restype = C.c_int
-        L.chunkft_wgrad_adamw_fused_group.argtypes = [C.POINTER(GroupSegment), C.c_int32, C.POINTER(AdamWHparams),
-                                                      C.c_void_p, C.c_size_t, C.c_void_p]
-        L.chunkft_wgrad_adamw_fused_static.restype = C.c_int
-        L.chunkft_wgrad_adamw_fused_static.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64, C.c_void_p,
-                                                       C.c_void_p, C.c_void_p, C.c_void_p,
-                                                       C.POINTER(AdamWHparams), C.c_void_p]
-        L.chunkft_status_string.restype = C.c_char_p
-        L.chunkft_status_string.argtypes = [C.c_int]
-        L.chunkft_version.restype = C.c_int
-        L.chunkft_version.argtypes = []
-        L.chunkft_mover_create.restype = C.c_int
-        L.chunkft_mover_create.argtypes = [C.POINTER(C.c_void_p)]
-        L.chunkft_mover_destroy.restype = None
-        L.chunkft_mover_destroy.argtypes = [C.c_void_p]
-        L.chunkft_mover_load.restype = C.c_int
-        L.chunkft_mover_load.argtypes = [C.c_void_p] + [C.c_void_p] * 6 + [C.c_int64, C.c_void_p]
-        L.chunkft_mover_await_load.restype = C.c_int
-        L.chunkft_mover_await_load.argtypes = [C.c_void_p, C.c_void_p]
-        L.chunkft_mover_offload.restype = C.c_int
-        L.chunkft_mover_offload.argtypes = [C.c_void_p] + [C.c_void_p] * 6 + [C.c_int64, C.c_void_p]
-        L.chunkft_mover_sync.restype = C.c_int
-        L.chunkft_mover_sync.argtypes = [C.c_void_p]
-        L.chunkft_schedule_at.restype = C.c_int
-        L.chunkft_schedule_at.argtypes = [C.c_int64, C.c_int32, C.c_int64, C.POINTER(ScheduleEntry)]
-        L.chunkft_calib_mfma_bf16_shape.restype = C.c_int
-        L.chunkft_calib_mfma_bf16_shape.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t,
-                                                    C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]
-        L.chunkft_calib_mfma_bf16.restype = C.c_int
-        L.chunkft_calib_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.POINTER(C.c_double),
-                                              C.POINTER(C.c_double), C.c_void_p]
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} is missing: build it with `python -m paper_2605_21177_amd.build` "
+            "(there is no fallback path)")
+    L = C.CDLL(path)
+    L.chunkft_plan_cycle.restype = C.c_int
+    L.chunkft_plan_cycle.argtypes = [C.POINTER(TensorDesc), C.c_int32, C.c_int64, C.c_uint32,
+                                     C.POINTER(Chunk), C.c_int64, C.POINTER(C.c_int64),
+                                     C.POINTER(Segment), C.c_int64, C.POINTER(C.c_int64)]
+    L.chunkft_plan_stats.restype = C.c_int
+    L.chunkft_plan_stats.argtypes = [C.POINTER(Chunk), C.c_int64, C.c_int64, C.POINTER(PlanSummary)]
+    L.chunkft_split_k.restype = C.c_int
+    L.chunkft_split_k.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64]
+    L.chunkft_workspace_bytes.restype = C.c_size_t
+    L.chunkft_workspace_bytes.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64]
+    L.chunkft_chunk_wgrad.restype = C.c_int
+    L.chunkft_chunk_wgrad.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64, C.c_void_p, C.c_int,
+                                      C.c_void_p, C.c_size_t, C.c_void_p]
+    L.chunkft_adamw_chunk.restype = C.c_int
+    L.chunkft_adamw_chunk.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_int32, C.c_int64, C.POINTER(AdamWHparams), C.c_void_p]
+    L.chunkft_wgrad_adamw_fused.restype = C.c_int
+    L.chunkft_wgrad_adamw_fused.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.POINTER(AdamWHparams), C.c_void_p, C.c_size_t,
+                                            C.c_void_p]
+    L.chunkft_group_workspace_bytes.restype = C.c_size_t
+    L.chunkft_group_workspace_bytes.argtypes = [C.POINTER(GroupSegment), C.c_int32]
+    L.chunkft_wgrad_adamw_fused_group.restype = C.c_int
+    L.chunkft_wgrad_adamw_fused_group.argtypes = [C.POINTER(GroupSegment), C.c_int32, C.POINTER(AdamWHparams),
+                                                  C.c_void_p, C.c_size_t, C.c_void_p]
+    L.chunkft_wgrad_adamw_fused_static.restype = C.c_int
+    L.chunkft_wgrad_adamw_fused_static.argtypes = [C.POINTER(Layer), C.c_int64, C.c_int64, C.c_void_p,
+                                                   C.c_void_p, C.c_void_p, C.c_void_p,
+                                                   C.POINTER(AdamWHparams), C.c_void_p]
+    L.chunkft_status_string.restype = C.c_char_p
+    L.chunkft_status_string.argtypes = [C.c_int]
+    L.chunkft_version.restype = C.c_int
+    L.chunkft_version.argtypes = []
+    L.chunkft_mover_create.restype = C.c_int
+    L.chunkft_mover_create.argtypes = [C.POINTER(C.c_void_p)]
+    L.chunkft_mover_destroy.restype = None
+    L.chunkft_mover_destroy.argtypes = [C.c_void_p]
+    L.chunkft_mover_load.restype = C.c_int
+    L.chunkft_mover_load.argtypes = [C.c_void_p] + [C.c_void_p] * 6 + [C.c_int64, C.c_void_p]
+    L.chunkft_mover_await_load.restype = C.c_int
+    L.chunkft_mover_await_load.argtypes = [C.c_void_p, C.c_void_p]
+    L.chunkft_mover_offload.restype = C.c_int
+    L.chunkft_mover_offload.argtypes = [C.c_void_p] + [C.c_void_p] * 6 + [C.c_int64, C.c_void_p]
+    L.chunkft_mover_sync.restype = C.c_int
+    L.chunkft_mover_sync.argtypes = [C.c_void_p]
+    L.chunkft_schedule_at.restype = C.c_int
+    L.chunkft_schedule_at.argtypes = [C.c_int64, C.c_int32, C.c_int64, C.POINTER(ScheduleEntry)]
+    L.chunkft_calib_mfma_bf16_shape.restype = C.c_int
+    L.chunkft_calib_mfma_bf16_shape.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t,
+                                                C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]
+    L.chunkft_calib_mfma_bf16.restype = C.c_int
+    L.chunkft_calib_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.POINTER(C.c_double),
+                                          C.POINTER(C.c_double), C.c_void_p]
     return L
 
 
