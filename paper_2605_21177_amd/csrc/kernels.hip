@@ -307,7 +307,7 @@ __global__ __launch_bounds__(kEdgeThreads) void wgrad_edge_kernel(const EdgePara
   __syncthreads();
   if (threadIdx.x < kMaxEdgeRows * kEdgeCols && col_ok) {
     const int e = threadIdx.x / kEdgeCols;
-    const int64_t row = e < 8 ? q.lead_base + e : q.trail_row;
+    const int64_t row = e < 8 ? (has_lead ? q.lead_base + e : -1) : q.trail_row;   // -1: nothing to emit
     const int64_t flat = row * p.in + col;
     if (row >= 0 && flat >= p.begin && flat < p.end) {
       float sum = red[0][e][c];

@@ -178,6 +178,10 @@ RANGES_520x264 = [
     (264 * 6 + 1, 264 * 9 + 263),   # few rows: one body row between edge rows
     (264 * 1 + 1, 264 * 6 + 5),     # six rows, none of them in the 8-aligned body
     (264 * 259 + 263, 264 * 519),   # starts on the last element of a row
+    (0, 264 * 4 + 100),             # from the tensor's first row: four complete rows, the partial one in the same 8-row group
+    (0, 264 * 100 + 77),            # from the first row: a body of at most 128 rows and a partial last row
+    (264 * 8, 264 * 11 + 5),        # begin on an 8-aligned row boundary, three complete rows, a partial one
+    (264 * 16, 264 * 120 + 9),      # the same with a longer body that still leaves the edge rows to their own kernel
 ]
 
 
@@ -392,6 +396,16 @@ def test_self_normalising_scale_vectors(kind):
 
 def test_warm_state_second_step():
     _full_check(_small_bf16(seed=81), 264 * 2 + 33, 264 * 519 + 1, warm=True, step=2)
+
+
+@pytest.mark.parametrize("begin,end", [(0, 264 * 4 + 100), (0, 264 * 100 + 77), (264 * 8, 264 * 11 + 5),
+                                       (264 * 16, 264 * 120 + 9), (264 * 1 + 1, 264 * 6 + 5), (0, 264 * 300 + 100)])
+@pytest.mark.parametrize("split_k", [None, 2])
+def test_warm_state_on_ranges_with_separate_edge_rows(begin, end, split_k):
+    """Warm moments make a second update of an element visible (from m = v = 0 an update with a zero
+    gradient changes nothing but the weight decay): ranges whose edge rows go to their own kernel, with
+    and without leading rows, fused against the oracle and against the un-fused pair bit for bit."""
+    _full_check(_small_bf16(seed=83), begin, end, split_k=split_k, warm=True, step=3)
 
 
 # ------------------------------------------- scaled-down configurations 2-5
