@@ -360,6 +360,53 @@ def test_bf16_random_shapes_strides_ranges_and_splits(seed):
         H.check_fused_against_oracle(g_ref, th0, z, z, HP, 1, master, m, v, bits[b:e])
 
 
+@pytest.mark.parametrize("seed", [201, 202])
+def test_random_cases_of_every_kind_cold_and_warm(seed):
+    """Seeded random layers of every kind and dtype (fp32 and odd-shaped bf16 matrices on the plain-FMA
+    path, bf16 matrices on the MFMA path with forced splits, scale vectors, embedding tables, the two
+    self-normalising vectors), ranges that often start at the tensor's first element or on a row boundary
+    and are often only a few rows long, half of them with warm moments: everything _full_check checks."""
+    rng = np.random.default_rng(seed)
+    for it in range(40):
+        kind = rng.choice(["lin_f32", "lin_bf16_odd", "lin_bf16", "vec", "emb", "rms", "ln"])
+        dtype = WL.BF16 if rng.random() < 0.6 else WL.F32
+        T = int(rng.integers(1, 400))
+        sk = None
+        if kind == "lin_f32":
+            case = WL.linear_case(rng, "f", int(rng.integers(1, 300)), int(rng.integers(1, 300)), T, WL.F32, 1e-3)
+            sk = [None, None, 2, 3][int(rng.integers(0, 4))]
+        elif kind == "lin_bf16_odd":
+            case = WL.linear_case(rng, "o", int(rng.integers(1, 300)), int(rng.integers(1, 300)), T, WL.BF16, 1e-3)
+            sk = [None, None, 2][int(rng.integers(0, 3))]
+        elif kind == "lin_bf16":
+            case = WL.linear_case(rng, "b", int(rng.integers(1, 120)) * 8, int(rng.integers(1, 120)) * 8, T, WL.BF16, 1e-3)
+            sk = [None, 1, 2, 3][int(rng.integers(0, 4))]
+        elif kind == "vec":
+            case = WL.vector_case(rng, "v", int(rng.integers(1, 5000)), T, dtype, 1e-3)
+        elif kind == "emb":
+            case = WL.embedding_case(rng, "e", int(rng.integers(1, 400)), int(rng.integers(1, 2200)), T, dtype, 1e-3)
+        else:
+            case = WL.norm_case(rng, "n", int(rng.integers(2, 5000)), T, dtype, 1e-3,
+                                WL.RMSNORM if kind == "rms" else WL.LAYERNORM)
+        if sk is not None and sk > T:
+            sk = None
+        N = case.numel
+        b = int(rng.integers(0, N))
+        e = int(rng.integers(b + 1, N + 1))
+        r = rng.random()
+        if r < 0.25:
+            b = 0
+        elif r < 0.5:
+            b = (b // case.n_in) * case.n_in
+        if rng.random() < 0.3:
+            e = min(N, b + int(rng.integers(1, 12 * case.n_in + 1)))
+        e = max(e, b + 1)
+        warm = bool(rng.random() < 0.5)
+        print(f"[case {it}] {kind} dtype {case.dtype} {case.out} x {case.n_in}, T {T}, [{b}, {e}), split {sk}, warm {warm}",
+              flush=True)
+        _full_check(case, b, e, split_k=sk, warm=warm, step=3 if warm else 1)
+
+
 def test_vector_kind():
     rng = np.random.default_rng(80)
     for dtype in (WL.BF16, WL.F32):
@@ -487,6 +534,74 @@ def test_grouped_call_equals_one_call_per_segment(budget_mib_x16, rows8):
     for k, (s0, s1, numel, _) in enumerate(a[0]):                 # and the grouped call did update every segment
         for (t, lo, hi, off) in a[1][s0:s1]:
             assert not torch.equal(b[3][k][off:off + hi - lo], layers[t].W0.reshape(-1)[lo:hi].float().to(H.DEV))
+
+
+@pytest.mark.parametrize("seed", [301, 302])
+def test_grouped_call_on_random_groups_of_every_kind(seed):
+    """Seeded random groups of one to eight segments (bf16 matrices with a forced token split of 1 - 3, bf16
+    scale vectors, embedding tables, self-normalising vectors, fp32 and odd-shaped matrices), the first
+    segment starting and the last one ending anywhere, warm moments: the grouped call equals one fused
+    call per segment bit for bit, and nothing is written outside a segment's arrays."""
+    rng = np.random.default_rng(seed)
+    for it in range(25):
+        nseg = int(rng.integers(1, 9))
+        T = int(rng.integers(1, 700))
+        segs, desc = [], []
+        for s in range(nseg):
+            kind = rng.choice(["lin", "lin", "lin", "vec", "emb", "norm", "f32", "odd"])
+            if kind == "emb":
+                case = WL.embedding_case(rng, "e", int(rng.integers(1, 300)), int(rng.integers(1, 600)), T,
+                                         WL.BF16 if rng.random() < 0.5 else WL.F32, 1e-3)
+            elif kind == "norm":
+                case = WL.norm_case(rng, "n", int(rng.integers(2, 3000)), T, WL.BF16, 1e-3,
+                                    WL.RMSNORM if rng.random() < 0.5 else WL.LAYERNORM)
+            elif kind == "f32":
+                case = WL.linear_case(rng, "f", int(rng.integers(1, 200)), int(rng.integers(1, 200)), T, WL.F32, 1e-3)
+            elif kind == "odd":
+                case = WL.linear_case(rng, "o", int(rng.integers(1, 200)), int(rng.integers(1, 200)), T, WL.BF16, 1e-3)
+            elif kind == "vec":
+                case = WL.vector_case(rng, "v", int(rng.integers(1, 200)) * 8, T, WL.BF16, 1e-3)
+            else:
+                case = WL.linear_case(rng, "m", int(rng.integers(1, 200)) * 8, int(rng.integers(1, 200)) * 8, T, WL.BF16, 1e-3)
+            N = case.numel
+            b = 0 if s > 0 else int(rng.integers(0, N))
+            e = N if s < nseg - 1 else int(rng.integers(b + 1, N + 1))
+            sk = int(rng.choice([1, 1, 1, 1, 2, 3]))      # a forced split: the grouped call obeys it as the single call does
+            if sk > T or kind in ("vec", "emb", "norm"):
+                sk = 0
+            segs.append((H.DeviceLayer(case, sk), b, e, case))
+            desc.append(f"{kind} {case.out} x {case.n_in} [{b}, {e}) split {sk}")
+        print(f"[case {it}] T {T}: " + " | ".join(desc), flush=True)
+
+        def run(grouped):
+            outs, calls, fulls = [], [], []
+            for si, (dl, b, e, case) in enumerate(segs):
+                n = e - b
+                gen = torch.Generator().manual_seed(1000 * it + si)
+                fm, master = H.guarded(n, case.W0.reshape(-1)[b:e].float())
+                fmm, m = H.guarded(n, torch.randn(n, generator=gen) * 1e-3)
+                fv, v = H.guarded(n, (0.25 + torch.randn(n, generator=gen) ** 2) * 1e-6)
+                W = case.W0.reshape(-1).clone().to(H.DEV)
+                outs.append((W, master, m, v))
+                fulls += [fm, fmm, fv]
+                calls.append((dl.layer(), b, e, W, master, m, v))
+            hp = B.hparams(step=3, **HP)
+            if grouped:
+                B.GroupCall(calls, device=H.DEV)(hp)
+            else:
+                for layer, b, e, W, master, m, v in calls:
+                    ws = H.workspace_for(layer, b, e)
+                    B.chunkft_wgrad_adamw_fused(layer, b, e, W, master, m, v, hp, ws=ws)
+                    torch.cuda.synchronize()
+                    assert H.workspace_intact(ws)
+            torch.cuda.synchronize()
+            assert all(H.guards_intact(f) for f in fulls), "state written outside a segment"
+            return outs
+
+        single, group = run(False), run(True)
+        for si, (a, g) in enumerate(zip(single, group)):
+            for name, x, y in zip(("W", "master", "m", "v"), a, g):
+                assert torch.equal(x, y), f"case {it} segment {si} ({desc[si]}): {name} differs"
 
 
 def test_grouped_call_runs_what_its_kernel_cannot_take_by_itself():
