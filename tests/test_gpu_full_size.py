@@ -165,7 +165,6 @@ def check_segment(case, dl, begin, end, *, split_k=None, fused=True, n_rows=8, n
                                 B.hparams(step=1, **HP), ws=ws)
     torch.cuda.synchronize()
     assert H.guards_intact(fm) and H.guards_intact(fmm) and H.guards_intact(fv)
-    assert H.workspace_intact(ws)
     W0d = W0.to(H.DEV)
     assert torch.equal(Wd[:begin].view(torch.int16), W0d[:begin].view(torch.int16))
     assert torch.equal(Wd[end:].view(torch.int16), W0d[end:].view(torch.int16))
@@ -197,6 +196,23 @@ def check_segment(case, dl, begin, end, *, split_k=None, fused=True, n_rows=8, n
         H.check_fused_against_oracle(ref_rows.reshape(-1), th0_r, zero, zero, HP, 1,
                                      master[idx_d].cpu().numpy(), m[idx_d].cpu().numpy(),
                                      v[idx_d].cpu().numpy(), bits)
+
+    # --- every element, two steps: the fused call equals the plain gradient followed by the AdamW call bit
+    # for bit (the second step starts from warm moments, where an element updated twice or not at all shows)
+    master_u, m_u, v_u = th0_dev.clone(), torch.zeros_like(th0_dev), torch.zeros_like(th0_dev)
+    Wu = W0.clone().to(H.DEV) if is_bf16 else None
+    for step in (1, 2):
+        if step == 2:
+            B.chunkft_wgrad_adamw_fused(layer, begin, end, Wd if is_bf16 else None, master, m, v,
+                                        B.hparams(step=2, **HP), ws=ws)
+        B.chunkft_adamw_chunk(g, master_u, m_u, v_u, Wu[begin:end] if is_bf16 else None, E, B.hparams(step=step, **HP),
+                              w_dtype=B.BF16 if is_bf16 else B.F32)
+        torch.cuda.synchronize()
+        assert torch.equal(master, master_u) and torch.equal(m, m_u) and torch.equal(v, v_u), \
+            f"step {step}: fused call and un-fused pair differ"
+        if is_bf16:
+            assert torch.equal(Wd.view(torch.int16), Wu.view(torch.int16)), f"step {step}: low-precision copies differ"
+    assert H.guards_intact(fm) and H.guards_intact(fmm) and H.guards_intact(fv) and H.workspace_intact(ws)
     return g
 
 
