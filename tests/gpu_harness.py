@@ -17,7 +17,10 @@ Comparison rules (the tolerances the build is held to):
   finite-precision gradient can reproduce: elements with |g| < 1e-4 rms(g)
   are then only required to move by at most 2 lr (+ 1e-5 |theta|);
 * low-precision copy: bit-exact round-to-nearest-even of the GPU's own fp32
-  master, and within one bf16 step of the oracle's rounded value;
+  master, and within one bf16 step of the oracle's rounded value where a bf16
+  step is at least the 1e-5 of the largest parameter that the two masters may
+  differ by (|theta| >= 2.56e-3 max|theta|); closer to zero the rounded value is
+  within that difference plus one step of the oracle's master;
 * anything outside the chunk: bit-identical to before the call.
 """
 
@@ -218,12 +221,26 @@ def check_fused_against_oracle(g_ref, th0, m0, v0, hp, step, master, m, v, W_bit
     assert ill.sum() <= 3 + 5e-4 * ill.size, f"too many tiny-gradient elements: {int(ill.sum())} of {ill.size}"
     if ill.any():
         moved = np.abs(np.asarray(master, np.float64)[ill] - np.asarray(th0, np.float64)[ill])
-        assert np.all(moved <= 2 * hp["lr"] + 1e-5 * np.abs(np.asarray(th0, np.float64)[ill]) + 1e-12)
+        assert np.all(moved <= 2 * hp["lr"] + 1e-5 * np.abs(np.asarray(th0, np.float64)[ill]) + 1e-12), \
+            "an element with a tiny gradient moved by more than two learning rates"
     if W_bits is not None:
         # bit-exact rounding of the GPU's own master, and one grid step from the oracle's
-        assert np.array_equal(W_bits, O.bf16_bits(np.asarray(master, dtype=np.float64)))
+        assert np.array_equal(W_bits, O.bf16_bits(np.asarray(master, dtype=np.float64))), \
+            "low-precision copy is not the round-to-nearest-even of the GPU's own master"
         ref_bits = O.bf16_bits(th_ref).astype(np.int64)
         ulp = np.abs(W_bits.astype(np.int64) - ref_bits)
-        # bit patterns of same-sign neighbours differ by 1; a tie between +-tiny values does not occur here
-        assert ulp[well].max() <= 1
+        # The two masters may differ by 1e-5 of the largest parameter (checked above).  Where a bf16 step
+        # (2^-8 of the value) is at least that large the two roundings are the same or neighbouring grid
+        # points (bit patterns of same-sign neighbours differ by 1); for the few parameters closer to zero
+        # the difference spans several of their much finer steps, and the rounded value itself is compared.
+        scale = float(np.max(np.abs(th_ref)))
+        coarse = well & (np.abs(th_ref) >= 256 * 1e-5 * scale)
+        if coarse.any():
+            assert ulp[coarse].max() <= 1, \
+                f"low-precision copy {int(ulp[coarse].max())} steps from the oracle's at element {int(np.argmax(ulp * coarse))}"
+        fine = well & ~coarse
+        if fine.any():
+            val = (W_bits[fine].astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+            assert np.all(np.abs(val - th_ref[fine]) <= 1e-5 * scale + np.abs(th_ref[fine]) / 256), \
+                "low-precision copy of a parameter near zero is off by more than the masters may differ"
     return th_ref, m_ref, v_ref
