@@ -359,6 +359,47 @@ def test_config4_full_size_down(config4_layers):
     check_segment(down, dl, 0, down.numel, n_rows=4, n_elems=500, seed=48)
 
 
+def test_config4_full_size_straddling_chunk_in_one_launch(config4_layers):
+    """The 128 MiB chunk that ends the gate projection and begins the down projection (two segments, both
+    on the 256 x 256 tile at this token count) through chunkft_wgrad_adamw_fused_group, two steps (the second
+    from warm moments): state and bf16 copies equal, bit for bit, one chunkft_wgrad_adamw_fused call per segment
+    (whose values the two tests above hold against the oracle)."""
+    gate, down = config4_layers
+    length, _, straddle = _config4_offsets(gate)
+    parts = [(gate, straddle, gate.numel, 0), (down, 0, straddle + length - gate.numel, gate.numel - straddle)]
+    dls = [H.DeviceLayer(gate), H.DeviceLayer(down)]
+    results = []
+    for grouped in (False, True):
+        Wd = [c.W0.reshape(-1).clone().to(H.DEV) for c, _, _, _ in parts]
+        fm, master = H.guarded(length)
+        for i, (c, b, e, off) in enumerate(parts):
+            master[off:off + (e - b)] = Wd[i][b:e].float()
+        fmm, m = H.guarded(length, torch.zeros(1).expand(length))
+        fv, v = H.guarded(length, torch.zeros(1).expand(length))
+        calls = [(dls[i].layer(), b, e, Wd[i], master[off:off + e - b], m[off:off + e - b], v[off:off + e - b])
+                 for i, (c, b, e, off) in enumerate(parts)]
+        group = B.GroupCall(calls, device=H.DEV) if grouped else None
+        if grouped:
+            assert group.ws_bytes == 0                     # the kernel takes both segments
+        for step in (1, 2):
+            hp = B.hparams(step=step, **HP)
+            if grouped:
+                group(hp)
+            else:
+                for (layer, b, e, W, ma, mm, vv) in calls:
+                    B.chunkft_wgrad_adamw_fused(layer, b, e, W, ma, mm, vv, hp)
+            torch.cuda.synchronize()
+        assert H.guards_intact(fm) and H.guards_intact(fmm) and H.guards_intact(fv)
+        results.append((Wd, (master, m, v)))
+    (Wa, sa), (Wb, sb) = results
+    for x, y, name in zip(sa, sb, ("master", "m", "v")):
+        assert torch.equal(x.view(torch.int32), y.view(torch.int32)), name
+    for i in range(2):
+        assert torch.equal(Wa[i].view(torch.int16), Wb[i].view(torch.int16)), f"W of tensor {i}"
+    # every element of the chunk was updated: no moment is left at zero where the gradient is not
+    assert int((sb[1] == 0).sum().item()) <= 8
+
+
 # ------------------------------------------------------------ configuration 5
 def test_config5_full_size_chunk_sweep():
     case = WL.config5()
