@@ -406,3 +406,63 @@ def test_config5_full_size_chunk_sweep():
     dl = H.DeviceLayer(case)
     for i, (begin, end) in enumerate(WL.config5_ranges(case)):
         check_segment(case, dl, begin, end, n_rows=4, n_elems=500, seed=50 + i)
+
+
+# ------------------------------------------------------------ flat indices past 32 bits
+def test_flat_element_indices_beyond_32_bits():
+    """A tensor of more than 2^31 elements (270000 x 8192) and a range that starts past element 2^31, mid-row:
+    the plain gradient and the fused call (warm moments) of a linear layer on the MFMA path, and the same
+    range of an embedding table, against the oracle; nothing outside the range changes.  The embedding's
+    reference is the oracle on the rows the range touches (token ids re-based to the first of them; tokens
+    that name other rows add nothing to the range)."""
+    out, n_in, T = 270000, 8192, 72
+    assert out * n_in > (1 << 31)
+    rng = np.random.default_rng([9917, 77])
+    begin = (1 << 31) + 4099
+    end = begin + 3 * MiB + 5
+    r0, r1 = begin // n_in, (end - 1) // n_in
+    gen = torch.Generator(device=H.DEV).manual_seed(771)
+    W = torch.zeros(out * n_in, dtype=torch.bfloat16, device=H.DEV)
+    W[begin - 4096:end + 4096] = (torch.randn(end - begin + 8192, device=H.DEV, generator=gen) * 0.02).to(torch.bfloat16)
+    W_before = W.clone()
+    hp = dict(HP)
+
+    def run(kind, Xh, dYh, g_ref, what):
+        _say(f"{what}: {out}x{n_in} [{begin},{end})")
+        Xd, dYd = Xh.to(H.DEV), dYh.to(H.DEV)
+        layer = B.make_layer(kind, Xd, dYd, out, n_in)
+        full_g, g = H.guarded(end - begin)
+        ws = H.workspace_for(layer, begin, end)
+        B.chunkft_chunk_wgrad(layer, begin, end, g, ws=ws)
+        torch.cuda.synchronize()
+        assert H.guards_intact(full_g)
+        assert H.rel_frobenius(g.cpu().numpy(), g_ref) <= 3e-3, what
+        th0 = W_before[begin:end].float().cpu().numpy()
+        m0 = (rng.standard_normal(end - begin) * 1e-3).astype(np.float32)
+        v0 = ((0.25 + rng.standard_normal(end - begin) ** 2) * 1e-6).astype(np.float32)
+        fm, master = H.guarded(end - begin, th0)
+        fmm, m = H.guarded(end - begin, m0)
+        fv, v = H.guarded(end - begin, v0)
+        W.copy_(W_before)
+        B.chunkft_wgrad_adamw_fused(layer, begin, end, W, master, m, v, B.hparams(step=2, **hp), ws=ws)
+        torch.cuda.synchronize()
+        assert H.guards_intact(fm) and H.guards_intact(fmm) and H.guards_intact(fv) and H.workspace_intact(ws)
+        assert torch.equal(W[:begin].view(torch.int16), W_before[:begin].view(torch.int16)), what
+        assert torch.equal(W[end:].view(torch.int16), W_before[end:].view(torch.int16)), what
+        H.check_fused_against_oracle(g_ref, th0, m0, v0, hp, 2, master.cpu().numpy(), m.cpu().numpy(),
+                                     v.cpu().numpy(), WL.bits_u16(W[begin:end].cpu()))
+
+    X = WL.normal(rng, (T, n_in), 1.0, WL.BF16)
+    dY = WL.normal(rng, (T, out), 1e-3, WL.BF16)
+    run(B.LINEAR, X, dY, O.chunk_wgrad(WL.as_f64(X), WL.as_f64(dY), begin, end, dense=False), "linear layer")
+    del X, dY
+
+    T_e = 600
+    ids = rng.integers(0, out, size=T_e)
+    inside = rng.random(T_e) < 0.6                      # most tokens name rows of the range, some of them the same row
+    ids[inside] = rng.integers(r0, r1 + 1, size=int(inside.sum()))
+    ids[:7] = r0 + 3
+    dYe = WL.normal(rng, (T_e, n_in), 1e-3, WL.BF16)
+    hit = (ids >= r0) & (ids <= r1)
+    g_ref = O.embedding_wgrad(ids[hit] - r0, WL.as_f64(dYe)[hit], r1 - r0 + 1, begin - r0 * n_in, end - r0 * n_in)
+    run(B.EMBEDDING, torch.from_numpy(ids.astype(np.int64)), dYe, g_ref, "embedding table")
