@@ -42,6 +42,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--settle-steps", type=int, default=100,
+                    help="untimed steps before the warm-up steps (about 45 ms), so that the "
+                         "device's clock management has settled under the load (0: none)")
     ap.add_argument("--sweep", action="store_true",
                     help="also time the plain and the fused call at longer token counts (the same layer shape, "
                          "T = 4096 and 8192) and on the lm_head shape of configs[4] per chunk size; "
@@ -144,12 +147,25 @@ def main():
                                   fused=(Wb, stB, B.hparams(step=1, **hp)) if args.timeline == "fused" else None)), flush=True)
         return
 
+    # Settling: from idle the device needs some tens of milliseconds of this load before its clock
+    # management holds a steady state (the first handful of steps run fast, the next twenty to thirty
+    # 15 - 25 % slow, then the times level off).  These steps are untimed and come before the W warm-up
+    # steps; their gradient times are reported as they were (settling) so the transient is on record.
+    settle_us = []
+    n_settle = max(args.settle_steps, 0)
+    for i in range(n_settle):
+        step(i, True)
+    torch.cuda.synchronize()
+    if n_settle:
+        settle_us = [round(a.elapsed_time(b) * 1e3, 1) for a, b in ev["wgrad"]]
+        for n in names:
+            ev[n].clear()
     for i in range(args.warmup):
-        step(i, False)
+        step(n_settle + i, False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(args.warmup + i, True)
+        step(n_settle + args.warmup + i, True)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -251,6 +267,12 @@ def main():
                         f"[{begin},{end}) (row span {R}), fp32 master/m/v for the chunk only",
             "step": "plan_cycle + chunk_wgrad + adamw_chunk + wgrad_adamw_fused",
             "split_k": S,
+            "settling": {"what": "untimed steps before the warm-up steps until the clock management holds a steady "
+                                 "state under this load; the gradient call's time in each of them, in order",
+                         "steps": n_settle,
+                         "wgrad_us_steps_2_to_9": settle_us[1:9],
+                         "wgrad_us_slowest_after_the_first": max(settle_us[1:]) if len(settle_us) > 1 else None,
+                         "wgrad_us_last_8": settle_us[-8:]},
             "chunk_arrays": "g, master, m, v at the 128-byte phase of the tensor rows (element i of an array "
                             "has the address phase of element begin + i of W); master, m, v cut from one "
                             "allocation, a whole number of MiB + 256 KiB apart (binding.chunk_state)",
