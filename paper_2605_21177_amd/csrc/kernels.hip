@@ -256,72 +256,108 @@ struct RingCfg {
                 "the main loop is written out for this shape");
 };
 
-// Edge rows: the leading ones all lie in one 8-aligned group of rows (one 16-byte
-// piece of dY per token), the trailing one is a single row.  One workgroup per
-// 32 columns; thread (tg, c) owns column c and the tokens t = tg (mod 32).  The
-// loads of kEdgeUnroll tokens are issued together, so a trip costs one memory
-// latency.  The 32 token-group partials meet in LDS and are added in group order.
+// Edge rows of a chunk whose body is too short to carry them in the MFMA kernel: the leading ones all
+// lie in one 8-aligned group of rows (one 16-byte piece of dY per token), the trailing one is a single
+// row.  A block is 32 columns over all tokens, done by 512 (token group, 8-column group) pairs -- 8
+// "virtual waves" of 64 lanes, lane l = 8-column group l % 4 of token group 16 vw + l / 4, tokens
+// t = token group (mod 128) in ascending order: per token one 16-byte piece of X, one of dY and the
+// trailing row's value feed 72 FMAs (with one column and 2-byte loads per lane the kernel was bound by
+// its load instructions: 300 us at 4096 tokens, eight times what it takes now).  The 16 token groups
+// of a virtual wave are added by a butterfly over the lanes, the 8 virtual waves meet in LDS and are
+// added in order.  A workgroup of NT threads takes the virtual waves NT / 64 at a time; the sums do not
+// depend on NT.
 constexpr int kEdgeCols = 32;
-constexpr int kEdgeTG = 16;
-constexpr int kEdgeThreads = kEdgeCols * kEdgeTG;
-constexpr int kEdgeUnroll = 32;
+constexpr int kEdgeVW = 8;                        // virtual waves per block
+constexpr int kEdgeTG = 16 * kEdgeVW;             // token groups
+constexpr int kEdgeThreads = 64 * kEdgeVW;
+constexpr int kEdgeUnroll = 4;
 
-template <int MODE>
-__global__ __launch_bounds__(kEdgeThreads) void wgrad_edge_kernel(const EdgeParams q) {
-  __shared__ float red[kEdgeTG][kMaxEdgeRows][kEdgeCols];
-  const WgradProblem& p = q.p;
-  const int c = threadIdx.x & (kEdgeCols - 1), tg = threadIdx.x / kEdgeCols;
-  const int64_t col = (int64_t)blockIdx.x * kEdgeCols + c;
-  const bool col_ok = col < p.in;
+template <int NT, int MODE>
+__device__ __forceinline__ void edge_rows_block(const WgradProblem& p, const Sinks& s, const int64_t lead_base,
+                                                const int64_t trail_row, const int64_t block,
+                                                float (*red)[kMaxEdgeRows][kEdgeCols]) {
+  static_assert(NT % 64 == 0 && kEdgeThreads % NT == 0, "whole virtual waves per pass");
   const unsigned short* X = (const unsigned short*)p.X;
   const unsigned short* dY = (const unsigned short*)p.dY;
-  const bool has_lead = q.lead_base >= 0, has_trail = q.trail_row >= 0;
-  float acc[kMaxEdgeRows];
+  const bool has_lead = lead_base >= 0, has_trail = trail_row >= 0;
+  const int lane = threadIdx.x & 63;
+  const int cg = lane & 3, tgl = lane >> 2;
+  const int64_t col8 = block * kEdgeCols + cg * 8;               // in % 8 == 0: a group of 8 columns is whole or absent
+  const bool col_ok = col8 < p.in;
+  for (int vw = threadIdx.x >> 6; vw < kEdgeVW; vw += NT / 64) {
+    float acc[kMaxEdgeRows][8];
 #pragma unroll
-  for (int e = 0; e < kMaxEdgeRows; ++e) acc[e] = 0.f;
-  for (int64_t t0 = tg; t0 < p.T; t0 += (int64_t)kEdgeTG * kEdgeUnroll) {
-    unsigned short xs[kEdgeUnroll], tr[kEdgeUnroll];
-    uint4 ld[kEdgeUnroll];
+    for (int e = 0; e < kMaxEdgeRows; ++e)
 #pragma unroll
-    for (int u = 0; u < kEdgeUnroll; ++u) {
-      const int64_t t = t0 + (int64_t)u * kEdgeTG;
-      const bool ok = t < p.T && col_ok;
-      xs[u] = ok ? X[t * p.ldx + col] : (unsigned short)0;
-      ld[u] = (ok && has_lead) ? *(const uint4*)(dY + t * p.lddy + q.lead_base) : make_uint4(0, 0, 0, 0);
-      tr[u] = (ok && has_trail) ? dY[t * p.lddy + q.trail_row] : (unsigned short)0;
-    }
+      for (int c = 0; c < 8; ++c) acc[e][c] = 0.f;
+    for (int64_t t0 = vw * 16 + tgl; t0 < p.T; t0 += (int64_t)kEdgeTG * kEdgeUnroll) {
+      uint4 xs[kEdgeUnroll], ld[kEdgeUnroll];
+      unsigned short tr[kEdgeUnroll];
 #pragma unroll
-    for (int u = 0; u < kEdgeUnroll; ++u) {
-      const float x = bf16_bits_to_f32(xs[u]);
-      const unsigned int w[4] = {ld[u].x, ld[u].y, ld[u].z, ld[u].w};
-#pragma unroll
-      for (int h = 0; h < 4; ++h) {
-        acc[2 * h] = fmaf(__uint_as_float(w[h] << 16), x, acc[2 * h]);
-        acc[2 * h + 1] = fmaf(__uint_as_float(w[h] & 0xffff0000u), x, acc[2 * h + 1]);
+      for (int u = 0; u < kEdgeUnroll; ++u) {
+        const int64_t t = t0 + (int64_t)u * kEdgeTG;
+        const bool ok = t < p.T && col_ok;
+        xs[u] = ok ? *(const uint4*)(X + t * p.ldx + col8) : make_uint4(0, 0, 0, 0);
+        ld[u] = (ok && has_lead) ? *(const uint4*)(dY + t * p.lddy + lead_base) : make_uint4(0, 0, 0, 0);
+        tr[u] = (ok && has_trail) ? dY[t * p.lddy + trail_row] : (unsigned short)0;
       }
-      acc[8] = fmaf(bf16_bits_to_f32(tr[u]), x, acc[8]);
-    }
-  }
 #pragma unroll
-  for (int e = 0; e < kMaxEdgeRows; ++e) red[tg][e][c] = acc[e];
+      for (int u = 0; u < kEdgeUnroll; ++u) {
+        const unsigned int xw[4] = {xs[u].x, xs[u].y, xs[u].z, xs[u].w};
+        const unsigned int dw[4] = {ld[u].x, ld[u].y, ld[u].z, ld[u].w};
+        float x[8], d[kMaxEdgeRows];
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+          x[2 * h] = __uint_as_float(xw[h] << 16);
+          x[2 * h + 1] = __uint_as_float(xw[h] & 0xffff0000u);
+          d[2 * h] = __uint_as_float(dw[h] << 16);
+          d[2 * h + 1] = __uint_as_float(dw[h] & 0xffff0000u);
+        }
+        d[8] = bf16_bits_to_f32(tr[u]);
+#pragma unroll
+        for (int e = 0; e < kMaxEdgeRows; ++e)
+#pragma unroll
+          for (int c = 0; c < 8; ++c) acc[e][c] = fmaf(d[e], x[c], acc[e][c]);
+      }
+    }
+    // the 16 token groups of this virtual wave: lanes that differ in bits 2-5
+#pragma unroll
+    for (int e = 0; e < kMaxEdgeRows; ++e)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        float v = acc[e][c];
+        v += __shfl_xor(v, 4);
+        v += __shfl_xor(v, 8);
+        v += __shfl_xor(v, 16);
+        v += __shfl_xor(v, 32);
+        if (tgl == 0) red[vw][e][cg * 8 + c] = v;
+      }
+  }
   __syncthreads();
-  if (threadIdx.x < kMaxEdgeRows * kEdgeCols && col_ok) {
-    const int e = threadIdx.x / kEdgeCols;
-    const int64_t row = e < 8 ? (has_lead ? q.lead_base + e : -1) : q.trail_row;   // -1: nothing to emit
+  for (int o = threadIdx.x; o < kMaxEdgeRows * kEdgeCols; o += NT) {
+    const int e = o / kEdgeCols, c = o & (kEdgeCols - 1);
+    const int64_t col = block * kEdgeCols + c;
+    const int64_t row = e < 8 ? (has_lead ? lead_base + e : -1) : trail_row;   // -1: nothing to emit
     const int64_t flat = row * p.in + col;
-    if (row >= 0 && flat >= p.begin && flat < p.end) {
+    if (col < p.in && row >= 0 && flat >= p.begin && flat < p.end) {
       float sum = red[0][e][c];
-      for (int g = 1; g < kEdgeTG; ++g) sum += red[g][e][c];
+      for (int g = 1; g < kEdgeVW; ++g) sum += red[g][e][c];
       const int64_t E = p.end - p.begin, i = flat - p.begin;
       if constexpr (MODE == EMIT_PARTIAL) {
         // the edge rows take all tokens at once: slab 0 carries the sum, the rest zero
-        q.s.ws[i] = sum;
-        for (int32_t sl = 1; sl < p.S; ++sl) q.s.ws[(int64_t)sl * q.s.ws_pitch + i] = 0.f;
+        s.ws[i] = sum;
+        for (int32_t sl = 1; sl < p.S; ++sl) s.ws[(int64_t)sl * s.ws_pitch + i] = 0.f;
       } else {
-        emit<MODE>(q.s, E, 0, i, flat, sum);
+        emit<MODE>(s, E, 0, i, flat, sum);
       }
     }
   }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kEdgeThreads) void wgrad_edge_kernel(const EdgeParams q) {
+  __shared__ float red[kEdgeVW][kMaxEdgeRows][kEdgeCols];
+  edge_rows_block<kEdgeThreads, MODE>(q.p, q.s, q.lead_base, q.trail_row, blockIdx.x, red);
 }
 
 
