@@ -239,9 +239,13 @@ def main():
     torch.cuda.synchronize()
     wgrad_loop_ms = float(np.median([a.elapsed_time(b) for a, b in pairs]))
 
-    lib_view_ms = lib_gemm_ms(dY[:, r_first:r_first + R])                  # the chunk's own row span, as it lies in dY
     R_even = E // case.n_in
-    lib_copy_ms = lib_gemm_ms(dY[:, r_first:r_first + R_even].contiguous())  # E / in whole rows, packed
+    try:
+        lib_view_ms = lib_gemm_ms(dY[:, r_first:r_first + R])                  # the chunk's own row span, as it lies in dY
+        lib_copy_ms = lib_gemm_ms(dY[:, r_first:r_first + R_even].contiguous())  # E / in whole rows, packed
+    except RuntimeError as ex:                                                   # the yardstick must not cost the result
+        print(f"bench.py: library GEMM yardstick failed: {ex}", file=sys.stderr)
+        lib_view_ms = lib_copy_ms = float("nan")
     wgrad_bytes = 2.0 * T * case.n_in + 2.0 * T * R + 4.0 * E        # X once, dY columns once, g once
     adamw_bytes = 30.0 * E                                            # g 4 + state 24 + bf16 W 2
     fused_bytes = 26.0 * E + 2.0 * T * (case.n_in + R)
@@ -299,10 +303,12 @@ def main():
                      "library_gemm": {
                          "what": "yardstick only, not part of the path: torch.mm (the vendor library's GEMM) of the "
                                  "transposed dY columns with X, bf16 result instead of fp32, median of 20",
-                         "chunk_rows_as_they_lie": {"rows": R, "ms": round(lib_view_ms, 4),
-                                                    "tflops": round(2.0 * T * R * case.n_in / (lib_view_ms * 1e-3) / 1e12, 2)},
-                         "whole_rows_packed": {"rows": R_even, "ms": round(lib_copy_ms, 4),
-                                               "tflops": round(2.0 * T * R_even * case.n_in / (lib_copy_ms * 1e-3) / 1e12, 2)}},
+                         "chunk_rows_as_they_lie": None if lib_view_ms != lib_view_ms else {
+                             "rows": R, "ms": round(lib_view_ms, 4),
+                             "tflops": round(2.0 * T * R * case.n_in / (lib_view_ms * 1e-3) / 1e12, 2)},
+                         "whole_rows_packed": None if lib_copy_ms != lib_copy_ms else {
+                             "rows": R_even, "ms": round(lib_copy_ms, 4),
+                             "tflops": round(2.0 * T * R_even * case.n_in / (lib_copy_ms * 1e-3) / 1e12, 2)}},
                      "mfma_only_measured": {
                          "what": "32x32x16 bf16 MFMAs issued from registers, nothing else, two waves per SIMD "
                                  "(chunkft_calib_mfma_bf16): the sustained clock, hence the reachable rate, "
