@@ -610,14 +610,21 @@ def block_cycle(torch, B, dev, hp, reps=10, graph=True):
             "cycle_ms_per_segment_calls": round(sum(r["ms_per_segment_calls"] for r in rows), 4)}
 
 
-def _median_ms(torch, fn, reps=10, warm=2):
-    for _ in range(warm):
+def _median_ms(torch, fn, reps=10, warm=2, settle_ms=30.0):
+    """Median event time of `reps` calls issued back to back, after at least `warm` calls and `settle_ms`
+    of the same load (the device's clocks need that long from idle or from a lighter load, see main())."""
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(); fn(); b.record(); b.synchronize()
+    first = max(a.elapsed_time(b), 1e-3)
+    for _ in range(max(warm - 1, min(int(settle_ms / first), 400))):
         fn()
-    ts = []
+    pairs = []
     for _ in range(reps):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record(); fn(); b.record(); b.synchronize()
-        ts.append(a.elapsed_time(b))
+        a.record(); fn(); b.record()
+        pairs.append((a, b))
+    torch.cuda.synchronize()
+    ts = [a.elapsed_time(b) for a, b in pairs]
     return sorted(ts)[len(ts) // 2]
 
 
