@@ -239,6 +239,24 @@ def main():
     torch.cuda.synchronize()
     wgrad_loop_ms = float(np.median([a.elapsed_time(b) for a, b in pairs]))
 
+    # yardstick for the AdamW pass: a plain streaming kernel of the library over the same number of bytes
+    # (half read, half written), settled the same way
+    n_copy = int(30.0 * E / 2 / 4)
+    src = torch.randn(n_copy, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(80):
+        torch.mul(src, 1.0, out=dst)
+    pairs = []
+    for i in range(20):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        torch.mul(src, 1.0, out=dst)
+        b.record()
+        pairs.append((a, b))
+    torch.cuda.synchronize()
+    lib_copy_stream_ms = float(np.median([a.elapsed_time(b) for a, b in pairs]))
+    del src, dst
+
     R_even = E // case.n_in
     try:
         lib_view_ms = lib_gemm_ms(dY[:, r_first:r_first + R])                  # the chunk's own row span, as it lies in dY
@@ -323,7 +341,11 @@ def main():
         "roofline_adamw": {"kernel": "elementwise_kernel (chunkft_adamw_chunk)", "bound": "hbm",
                            "achieved": round(adamw_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                            "frac": round(adamw_gbps / PEAK_HBM_GBPS, 4), "traffic": MEASURED_TRAFFIC["adamw"],
-                           "algorithmic_bytes": adamw_bytes},
+                           "algorithmic_bytes": adamw_bytes,
+                           "library_copy": {"what": "yardstick only: torch.mul(src, 1.0, out=dst) over the same number "
+                                                    "of bytes, half read and half written, median of 20",
+                                            "ms": round(lib_copy_stream_ms, 4),
+                                            "gbps": round(2.0 * n_copy * 4 / (lib_copy_stream_ms * 1e-3) / 1e9, 1)}},
     }
 
     if not args.no_per_config:
