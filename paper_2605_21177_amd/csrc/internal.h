@@ -63,6 +63,7 @@ struct RowSplit {
   int64_t trail_row;    // partial last row outside the body, or -1
 };
 RowSplit split_rows(const WgradProblem& p);               // needs p.begin, p.end, p.in only
+bool plain_takes_large_tile(int64_t large_tiles, int64_t slab_tokens, int compute_units);   // tile of the plain gradient
 bool edge_rows_folded(const RowSplit& rs);                // the MFMA kernel carries the edge rows itself
 
 // Tile of the plain MFMA gradient and of the FMA kernel: what the token split is chosen from.

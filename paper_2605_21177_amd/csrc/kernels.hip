@@ -232,11 +232,12 @@ struct EdgeParams {
 //   compute unit, so the store-bound epilogue of one runs under the MFMA loop of the other;
 //   WM = 2, NS = 4: 256 x 256 tiles, 8 waves, 132 KB -- one workgroup per compute unit,
 //   a third less operand traffic per flop.
-template <int WM_, int NS_>
+template <int WM_, int NS_, int MI_ = 32>
 struct RingCfg {
   static constexpr int WM = WM_, WN = 4, BM = 128 * WM, BN = 256, BK = 32, NS = NS_;
+  static constexpr int MI = MI_;                      // MFMA shape: 32 (32x32x16) or 16 (16x16x32)
   static constexpr int NW = WM * WN, NT = 64 * NW;
-  static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  static constexpr int TM = BM / WM / MI, TN = BN / WN / MI;
   static constexpr int A_BYTES = BK * BM * 2, B_BYTES = BK * BN * 2;
   // edge block: per token 16 row values = the 8-row group of the leading edge rows and
   // the 8-row group that holds the trailing row (32 B per token, 1 KB per slab)
@@ -247,13 +248,15 @@ struct RingCfg {
   static constexpr int L = LA + LB;
   // epilogue staging: half a tile (BM / 2 rows x 256 columns of fp32) at a time; a row
   // pitch of 264 floats puts the two half-waves of a ds_write_b32 on disjoint banks
-  static constexpr int EPI_PITCH = BN + 8;
+  // (with the 16 x 16 blocks of the other MFMA shape a write spans four row groups: 260 floats spread them)
+  static constexpr int EPI_PITCH = MI == 32 ? BN + 8 : BN + 4;
   static constexpr size_t EPI_BYTES = (size_t)(BM / 2) * EPI_PITCH * 4;
   static constexpr size_t RING_BYTES = (size_t)NS * STAGE_BYTES;
   static constexpr size_t LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
   static constexpr int RA = BM * 2, RB = BN * 2;     // bytes of one token in the A / B image of a slab
-  static_assert(TM == 4 && TN == 2 && (WM == 1 || WM == 2) && L >= 4 && L <= 6 && NS >= 3,
-                "the main loop is written out for this shape");
+  static_assert((MI == 32 || MI == 16) && TM * MI == 128 && TN * MI == 64 && (WM == 1 || WM == 2) && L >= 4 &&
+                    L <= 6 && NS >= 3,
+                "the main loops are written out for this shape");
 };
 
 // Edge rows of a chunk whose body is too short to carry them in the MFMA kernel: the leading ones all
@@ -391,11 +394,12 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // LDS (the ring is free by now), half of it at a time, and leaves as whole rows:
 // a wave handles one row of 256 columns per trip, 16 bytes per lane, 1 KB per
 // instruction, for the gradient as well as for the AdamW state.
-template <class C, int MODE>
+// stage_half(h, stage, sft) writes the wave's share of half h into the staging area; emit_edge(E) emits
+// the edge block's elements (both know the accumulator layout of the MFMA shape in use).
+template <class C, int MODE, class StageHalf, class EmitEdge>
 __device__ __forceinline__ void tile_epilogue(const MfmaParams& q, unsigned char* ldsb, int64_t row0, int64_t col0,
                                               int slab, int wave, int lane, int tid,
-                                              f32x16 (&acc)[C::TM][C::TN], bool has_edge, int edge_blk,
-                                              const f32x16& acc_e) {
+                                              StageHalf&& stage_half, EmitEdge&& emit_edge) {
   const WgradProblem& p = q.p;
   const int wn0 = (wave % C::WN) * (C::BN / C::WN);
   const int64_t E = p.end - p.begin;
@@ -404,8 +408,7 @@ __device__ __forceinline__ void tile_epilogue(const MfmaParams& q, unsigned char
   const int cols_valid = (int)((p.in - col0 < C::BN) ? p.in - col0 : C::BN);
   float* const stage = reinterpret_cast<float*>(ldsb);
   const int wmi = wave / C::WN;
-  constexpr int APH = C::TM / 2;          // 32-row accumulator blocks of a wave per half
-  constexpr int WR = 32 * APH;            // rows of one wave row in a staged half
+  constexpr int WR = C::BM / C::WM / 2;   // rows of one wave row in a staged half
   constexpr int HALF_ROWS = C::WM * WR;   // rows staged per pass
   float* const g_dst = MODE == EMIT_PARTIAL ? q.s.ws + (int64_t)slab * q.s.ws_pitch : q.s.g;
   // Groups of four columns start where the fp32 destination is 16-byte aligned:
@@ -430,30 +433,11 @@ __device__ __forceinline__ void tile_epilogue(const MfmaParams& q, unsigned char
                                : (void*)((float*)q.s.W + i + p.begin);
     return d;
   };
-  if (has_edge) {
-    // Edge block: MFMA rows 0-7 are the leading group, 8-15 the group of the trailing row
-    // (registers v = 0..7 of the block); one element at a time, masked by the chunk's range.
-    const int64_t col = col0 + wn0 + edge_blk * 32 + (lane & 31);
-#pragma unroll
-    for (int v = 0; v < 8; ++v) {
-      const int r8 = (lane >> 5) * 4 + (v & 3);
-      int64_t row;
-      if (v < 4) row = q.lead_base >= 0 ? q.lead_base + r8 : -1;
-      else row = (q.trail_row >= 0 && (q.trail_row & 7) == r8) ? q.trail_row : -1;
-      const int64_t flat = row * p.in + col;
-      if (row >= 0 && col < p.in && flat >= p.begin && flat < p.end)
-        emit<MODE>(q.s, E, slab, flat - p.begin, flat, acc_e[v]);
-    }
-  }
+  emit_edge(E);
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     __syncthreads();                       // ring reads / previous half's row reads are done
-    static_for<APH * C::TN>([&](auto blk_c) {
-      constexpr int a2 = decltype(blk_c)::value / C::TN, b = decltype(blk_c)::value % C::TN;
-      float* base = stage + (wmi * WR + a2 * 32 + (lane >> 5) * 4) * C::EPI_PITCH + sft + wn0 + b * 32 + (lane & 31);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) base[((v >> 2) * 8 + (v & 3)) * C::EPI_PITCH] = acc[h * APH + a2][b][v];
-    });
+    stage_half(h, stage + (wmi * WR) * C::EPI_PITCH + sft + wn0);
     __syncthreads();
     // The left-over element of this thread (delta != 0): in the fused call its state is requested
     // now and used after the row loop, so that this second round of loads costs no extra wait.
@@ -900,7 +884,446 @@ __device__ __forceinline__ void mfma_tile(const MfmaParams& q, const int item, u
   if (has_edge) run_slabs(IntC<1>{}); else run_slabs(IntC<0>{});
   TIMELINE_STAMP(q, item, 2);
 
-  tile_epilogue<C, MODE>(q, ldsb, row0, col0, slab, wave, lane, tid, acc, has_edge, edge_blk, acc_e);
+  // accumulator register v of a 32 x 32 block: row (v / 4) * 8 + (lane / 32) * 4 + v % 4, column lane % 32
+  auto stage_half = [&](int h, float* dst) {      // dst: the wave's first row and column in the staging area
+    static_for<(C::TM / 2) * C::TN>([&](auto blk_c) {
+      constexpr int a2 = decltype(blk_c)::value / C::TN, b = decltype(blk_c)::value % C::TN;
+      float* base = dst + (a2 * 32 + (lane >> 5) * 4) * C::EPI_PITCH + b * 32 + (lane & 31);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float x = h == 0 ? acc[a2][b][v] : acc[C::TM / 2 + a2][b][v];
+        base[((v >> 2) * 8 + (v & 3)) * C::EPI_PITCH] = x;
+      }
+    });
+  };
+  auto emit_edge = [&](int64_t E) {
+    if (!has_edge) return;
+    // Edge block: MFMA rows 0-7 are the leading group, 8-15 the group of the trailing row
+    // (registers v = 0..7 of the block); one element at a time, masked by the chunk's range.
+    const int64_t col = col0 + wn0 + edge_blk * 32 + (lane & 31);
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+      const int r8 = (lane >> 5) * 4 + (v & 3);
+      int64_t row;
+      if (v < 4) row = q.lead_base >= 0 ? q.lead_base + r8 : -1;
+      else row = (q.trail_row >= 0 && (q.trail_row & 7) == r8) ? q.trail_row : -1;
+      const int64_t flat = row * p.in + col;
+      if (row >= 0 && col < p.in && flat >= p.begin && flat < p.end)
+        emit<MODE>(q.s, E, slab, flat - p.begin, flat, acc_e[v]);
+    }
+  };
+  tile_epilogue<C, MODE>(q, ldsb, row0, col0, slab, wave, lane, tid, stage_half, emit_edge);
+  TIMELINE_STAMP(q, item, 3);
+}
+
+// The same tile with the 16x16x32 MFMA (which holds a higher clock under the part's power limit).
+// A wave's 128 x 64 sub-tile is 8 x 4 blocks of 16 x 16; an MFMA takes all 32 tokens of a slab, so
+// a slab is 32 MFMAs in two halves of 16: the upper four row blocks, then the lower four, each against
+// the slab's four column blocks.  Operand layout of the MFMA: lane l holds row (column) l % 16 and the
+// 8 tokens 8 (l / 16) ... + 7; a transpose read hands a 16-lane block 4 tokens of 16 rows, so an
+// operand block is two reads (tokens +0..3, +4..7).  A half-wave of such a read touches 8 tokens x 32
+// bytes; the 16-byte slots of a token row are therefore XOR-swizzled in bits 1-3 by
+// (k & 3) | ((k >> 3 & 1) << 2), which puts the 8 tokens on the 8 different 32-byte groups of the
+// 256-byte bank window (applied to the source offsets of the global->LDS loads, as in the other form).
+// Registers: the MFMAs of a half go column block by column block, so that in the lower half a
+// column block's registers are free after its four MFMAs and take the next slab's block at once; the
+// row blocks of one half are read while the other half's MFMAs run.  The ring keeps the A images of
+// all slabs together, then the B images, then the edge blocks: every read of an operand block is then
+// one base register plus an immediate offset, whatever the ring slot.
+#define WAIT8(h)                                                                                         \
+  asm volatile("s_waitcnt lgkmcnt(0)"                                                                    \
+               : "+v"(h[0]), "+v"(h[1]), "+v"(h[2]), "+v"(h[3]), "+v"(h[4]), "+v"(h[5]), "+v"(h[6]),     \
+                 "+v"(h[7])::"memory")
+#define WAIT8_8_2(ha, hb, he)                                                                            \
+  asm volatile("s_waitcnt lgkmcnt(0)"                                                                    \
+               : "+v"(ha[0]), "+v"(ha[1]), "+v"(ha[2]), "+v"(ha[3]), "+v"(ha[4]), "+v"(ha[5]),           \
+                 "+v"(ha[6]), "+v"(ha[7]), "+v"(hb[0]), "+v"(hb[1]), "+v"(hb[2]), "+v"(hb[3]),           \
+                 "+v"(hb[4]), "+v"(hb[5]), "+v"(hb[6]), "+v"(hb[7]), "+v"(he[0]), "+v"(he[1])::"memory")
+// all LDS reads but the last two issued (the next slab's last column block) have returned
+#define WAIT8_6_2_BUT2(ha, hb, he)                                                                       \
+  asm volatile("s_waitcnt lgkmcnt(2)"                                                                    \
+               : "+v"(ha[0]), "+v"(ha[1]), "+v"(ha[2]), "+v"(ha[3]), "+v"(ha[4]), "+v"(ha[5]),           \
+                 "+v"(ha[6]), "+v"(ha[7]), "+v"(hb[0]), "+v"(hb[1]), "+v"(hb[2]), "+v"(hb[3]),           \
+                 "+v"(hb[4]), "+v"(hb[5]), "+v"(he[0]), "+v"(he[1])::"memory")
+// the two reads issued before the last eight have returned
+#define WAIT2_BEFORE8(hb) asm volatile("s_waitcnt lgkmcnt(8)" : "+v"(hb[6]), "+v"(hb[7])::"memory")
+
+template <class C, int MODE>
+__device__ __forceinline__ void mfma_tile16(const MfmaParams& q, const int item, unsigned char* ldsb) {
+  static_assert(C::MI == 16 && C::TM == 8 && C::TN == 4, "written out for 8 x 4 blocks of 16 x 16 per wave");
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
+  const WgradProblem& p = q.p;
+  TIMELINE_STAMP(q, item, 0);
+#ifdef CHUNKFT_TIMELINE
+  if (q.timeline && threadIdx.x == 0)
+    q.timeline[(size_t)item * 8 + 4] = ((unsigned long long)__builtin_amdgcn_s_getreg((32 - 1) << 11 | 20) << 32) |
+                                       (unsigned)__builtin_amdgcn_s_getreg((32 - 1) << 11 | 4);
+#endif
+
+  // ---- which tile, which token slab (as in mfma_tile)
+  const int n_tiles = q.tiles_m * q.tiles_n;
+  const int slab = item / n_tiles;
+  const int tile = item - slab * n_tiles;
+  const int per_group = q.group_m * q.tiles_n;
+  const int grp = tile / per_group;
+  const int first_m = grp * q.group_m;
+  const int gsz = (q.tiles_m - first_m < q.group_m) ? q.tiles_m - first_m : q.group_m;
+  const int in_grp = tile - grp * per_group;
+  const int tile_m = first_m + in_grp % gsz;
+  const int tile_n = in_grp / gsz;
+  const int64_t row0 = q.rb0 + (int64_t)tile_m * C::BM;
+  const int64_t col0 = (int64_t)tile_n * C::BN;
+  const int64_t k_begin = (int64_t)slab * p.kslab;
+  const int64_t k_end = (k_begin + p.kslab < p.T) ? k_begin + p.kslab : p.T;
+  const int klen = (int)(k_end - k_begin);
+  const int nk = (klen + C::BK - 1) / C::BK;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm0 = (wave / C::WN) * (C::BM / C::WM);
+  const int wn0 = (wave % C::WN) * (C::BN / C::WN);
+  const unsigned short* dY = (const unsigned short*)p.dY;
+  const unsigned short* X = (const unsigned short*)p.X;
+  const unsigned lds_base = (unsigned)(uintptr_t)ldsb;
+
+  // ---- global->LDS loads (as in mfma_tile; the slot swizzle is the one described above)
+  // A wave's loads of one operand name tokens 4 apart (A) or 2 apart (B); tokens 4 apart have the same
+  // swizzle, so loads i and i + (4 tokens) share their per-lane offset and differ in a scalar offset.
+  constexpr int LPT_A = C::RA / 16, TPL_A = 64 / LPT_A;
+  constexpr int VA = TPL_A >= 4 ? 1 : (C::LA < 4 / TPL_A ? C::LA : 4 / TPL_A);   // distinct per-lane offsets
+  constexpr int VB = C::LB < 2 ? C::LB : 2;
+  unsigned voa[VA], vob[VB];
+  const unsigned lddy2 = (unsigned)(p.lddy * 2), ldx2 = (unsigned)(p.ldx * 2);
+  auto swz = [](int k) { return ((k & 3) | (((k >> 3) & 1) << 2)) << 1; };
+  auto tok_a = [&](int i) { return TPL_A * (wave * C::LA + i) + lane / LPT_A; };
+  auto tok_b = [&](int i) { return 2 * (wave * C::LB + i) + (lane >> 5); };
+  static_assert((TPL_A * C::LA == 4 || TPL_A * C::LA == 8) && (2 * C::LB == 4 || 2 * C::LB == 8),
+                "a wave's tokens of one operand are an aligned group of 4 or 8: tokens 4 apart share bit 3");
+#pragma unroll
+  for (int i = 0; i < VA; ++i) {
+    const int k = tok_a(i);
+    const int lc = (lane % LPT_A) ^ swz(k);
+    int64_t r = row0 + lc * 8;
+    if (r >= p.out) r = row0;
+    voa[i] = (unsigned)r * 2u + (unsigned)k * lddy2;
+  }
+#pragma unroll
+  for (int i = 0; i < VB; ++i) {
+    const int k = tok_b(i);
+    const int lc = (lane & 31) ^ swz(k);
+    int64_t cc = col0 + lc * 8;
+    if (cc >= p.in) cc = col0;
+    vob[i] = (unsigned)cc * 2u + (unsigned)k * ldx2;
+  }
+  const unsigned char* ga = (const unsigned char*)(dY + k_begin * p.lddy);
+  const unsigned char* gb = (const unsigned char*)(X + k_begin * p.ldx);
+  const int64_t stepA = (int64_t)C::BK * p.lddy * 2, stepB = (int64_t)C::BK * p.ldx * 2;
+  int next_fetch = 0;
+  auto load_to_lds = [&](const unsigned char* base, unsigned voff, unsigned soff, unsigned dst) {
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, -1, 0x00020000);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (LDS_PTR(void))(uintptr_t)dst, 16, (int)voff, (int)soff, 0, 0);
+  };
+  auto next_slab = [&]() {
+    ga += stepA;
+    gb += stepB;
+    ++next_fetch;
+  };
+
+  // ---- edge block: 16 rows per token (the 8-row group of the leading edge rows, the 8-row group of
+  // the trailing row), one 16 x 16 row block.  The two workgroups (waves) that share 64 columns take
+  // two of its four 16-column blocks each.
+  const bool has_edge = (C::WM == 2 ? tile_m == 0 : tile_m < 2) && (q.lead_base >= 0 || q.trail_row >= 0);
+  const int edge_blk = C::WM == 2 ? (wave >> 2) : tile_m;
+  const int ke = lane >> 1;
+  unsigned voe;
+  {
+    const int64_t lead = q.lead_base >= 0 ? q.lead_base : q.rb0;
+    const int64_t trail = q.trail_row >= 0 ? (q.trail_row & ~(int64_t)7) : q.rb0;
+    voe = (unsigned)((lane & 1) ? trail : lead) * 2u + (unsigned)ke * lddy2;
+  }
+  auto issue_edge = [&](auto stagec) {
+    constexpr int STAGE = decltype(stagec)::value;
+    const int stage = STAGE >= 0 ? STAGE : next_fetch % C::NS;
+    const bool ragged = STAGE >= 0 ? false : (next_fetch + 1) * C::BK > klen;
+    unsigned vo = voe;
+    if (ragged) {
+      const int64_t over = k_begin + (int64_t)next_fetch * C::BK + ke - (p.T - 1);
+      if (over > 0) vo -= (unsigned)over * lddy2;
+    }
+    load_to_lds(ga, vo, 0u, lds_base + C::NS * (C::A_BYTES + C::B_BYTES) + stage * C::E_BYTES);
+  };
+  auto issue_one = [&](auto idxc, auto stagec) {
+    constexpr int idx = decltype(idxc)::value, STAGE = decltype(stagec)::value;
+    const int stage = STAGE >= 0 ? STAGE : next_fetch % C::NS;
+    const bool ragged = STAGE >= 0 ? false : (next_fetch + 1) * C::BK > klen;
+    if constexpr (idx < C::LA) {
+      constexpr int i = idx;
+      unsigned vo = voa[i % VA];
+      if (ragged) {
+        const int64_t over = k_begin + (int64_t)next_fetch * C::BK + tok_a(i) - (p.T - 1);
+        if (over > 0) vo -= (unsigned)over * lddy2;
+      }
+      load_to_lds(ga, vo, (unsigned)(i / VA) * (unsigned)(TPL_A * VA) * lddy2,
+                  lds_base + stage * C::A_BYTES + (wave * C::LA + i) * 1024);
+    } else {
+      constexpr int i = idx - C::LA;
+      unsigned vo = vob[i % VB];
+      if (ragged) {
+        const int64_t over = k_begin + (int64_t)next_fetch * C::BK + tok_b(i) - (p.T - 1);
+        if (over > 0) vo -= (unsigned)over * ldx2;
+      }
+      load_to_lds(gb, vo, (unsigned)(i / VB) * (unsigned)(2 * VB) * ldx2,
+                  lds_base + C::NS * C::A_BYTES + stage * C::B_BYTES + (wave * C::LB + i) * 1024);
+    }
+  };
+
+  // ---- transpose-read addressing
+  const int blk = lane >> 4, i16 = lane & 15;
+  const int tr_k = blk * 8 + (i16 >> 2);                     // first of the 4 + 4 tokens this lane's reads name
+  const int swl = ((i16 >> 2) | ((blk & 1) << 2)) << 1;      // the swizzle of those tokens
+  const int low = (i16 & 3) >> 1;
+  const int sub = (i16 & 1) * 8;
+  static_assert((C::NS - 1) * C::A_BYTES + 4 * C::RA < 65536 && (C::NS - 1) * C::B_BYTES + 4 * C::RB < 65536,
+                "LDS offset field");
+  unsigned addrA[C::TM], addrB[C::TN];
+#pragma unroll
+  for (int a = 0; a < C::TM; ++a)
+    addrA[a] = lds_base + tr_k * C::RA + ((((wm0 >> 3) + a * 2) ^ swl) + low) * 16 + sub;
+#pragma unroll
+  for (int b = 0; b < C::TN; ++b)
+    addrB[b] = lds_base + C::NS * C::A_BYTES + tr_k * C::RB + ((((wn0 >> 3) + b * 2) ^ swl) + low) * 16 + sub;
+  const unsigned addrE = lds_base + C::NS * (C::A_BYTES + C::B_BYTES) + tr_k * 32 + (i16 & 3) * 8;
+
+  // Fragment halves: unit u of a row half is row block u / 2 of that half (tokens +0..3 if u is
+  // even, +4..7 if odd); unit u of the column set is column block u / 2 likewise.
+  bf16x4 ha0[8], ha1[8], hb[8], he[2];
+  // RH: which four row blocks (0: upper, 1: lower); st: ring slot
+  auto read_a = [&](bf16x4* h, auto rhc, int st, auto uc) {
+    constexpr int RH = decltype(rhc)::value, u = decltype(uc)::value;
+    h[u] = lds_tr_read<(u & 1) * 4 * C::RA>(addrA[4 * RH + u / 2] + (unsigned)(st * C::A_BYTES));
+  };
+  auto read_a_at = [&](bf16x4* h, auto rhc, auto stagec, auto uc) {
+    constexpr int RH = decltype(rhc)::value, st = decltype(stagec)::value, u = decltype(uc)::value;
+    h[u] = lds_tr_read<st * C::A_BYTES + (u & 1) * 4 * C::RA>(addrA[4 * RH + u / 2]);
+  };
+  auto read_b = [&](int st, auto uc) {
+    constexpr int u = decltype(uc)::value;
+    hb[u] = lds_tr_read<(u & 1) * 4 * C::RB>(addrB[u / 2] + (unsigned)(st * C::B_BYTES));
+  };
+  auto read_b_at = [&](auto stagec, auto uc) {
+    constexpr int st = decltype(stagec)::value, u = decltype(uc)::value;
+    hb[u] = lds_tr_read<st * C::B_BYTES + (u & 1) * 4 * C::RB>(addrB[u / 2]);
+  };
+  auto read_e = [&](int st) {
+    he[0] = lds_tr_read<0>(addrE + (unsigned)(st * C::E_BYTES));
+    he[1] = lds_tr_read<4 * 32>(addrE + (unsigned)(st * C::E_BYTES));
+  };
+  auto read_e_at = [&](auto stagec) {
+    constexpr int st = decltype(stagec)::value;
+    he[0] = lds_tr_read<st * C::E_BYTES>(addrE);
+    he[1] = lds_tr_read<st * C::E_BYTES + 4 * 32>(addrE);
+  };
+  auto frag = [&](const bf16x4* h, int u) {
+    return __builtin_shufflevector(h[u], h[u + 1], 0, 1, 2, 3, 4, 5, 6, 7);
+  };
+  // tokens past the end of a ragged last slab: zero in the row-block operands
+  auto mask_units = [&](bf16x4* h, int kt) {
+    if (kt == nk - 1 && (klen % C::BK) != 0) {
+      const int kv = klen - kt * C::BK - blk * 8;            // valid tokens among this lane's 8
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if ((u & 1) * 4 + e >= kv) h[u][e] = (__bf16)0.f;
+    }
+  };
+  auto mask_edge = [&](int kt) {
+    if (kt == nk - 1 && (klen % C::BK) != 0) {
+      const int kv = klen - kt * C::BK - blk * 8;
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (u * 4 + e >= kv) he[u][e] = (__bf16)0.f;
+    }
+  };
+
+  f32x4_t acc[C::TM][C::TN], acc_e[2];
+#pragma unroll
+  for (int a = 0; a < C::TM; ++a)
+#pragma unroll
+    for (int b = 0; b < C::TN; ++b)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc_e[j][v] = 0.f;
+
+  // ---- prologue: the whole ring in flight, the operands of slab 0's upper half in registers
+#pragma unroll
+  for (int s = 0; s < C::NS; ++s)
+    if (s < nk) {
+      static_for<C::L>([&](auto ic) { issue_one(ic, IntC<-1>{}); });
+      if (has_edge && wave == 0) issue_edge(IntC<-1>{});
+      next_slab();
+    }
+  const bool five = has_edge && wave == 0;
+  if (C::NS - 1 < nk) {
+    if (five) wait_vmcnt<(C::NS - 1) * (C::L + 1)>(); else wait_vmcnt<(C::NS - 1) * C::L>();
+  } else {
+    wait_vmcnt<0>();
+  }
+  __builtin_amdgcn_s_barrier();
+  static_for<8>([&](auto uc) { read_a(ha0, IntC<0>{}, 0, uc); });
+  static_for<8>([&](auto uc) { read_b(0, uc); });
+  he[0] = he[1] = bf16x4{};
+  if (has_edge) read_e(0);
+  WAIT8_8_2(ha0, hb, he);
+  mask_units(ha0, 0);
+  mask_edge(0);
+  TIMELINE_STAMP(q, item, 1);
+
+  // the edge MFMAs of a wave use two of its four column blocks (picked by value, as in mfma_tile)
+  auto edge_mma = [&]() {
+    const bf16x8 fe = __builtin_shufflevector(he[0], he[1], 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const u32x4_t lo = __builtin_bit_cast(u32x4_t, __builtin_shufflevector(hb[2 * j], hb[2 * j + 1], 0, 1, 2, 3, 4, 5, 6, 7));
+      const u32x4_t hi = __builtin_bit_cast(u32x4_t, __builtin_shufflevector(hb[4 + 2 * j], hb[5 + 2 * j], 0, 1, 2, 3, 4, 5, 6, 7));
+      u32x4_t bs;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) bs[e] = edge_blk == 0 ? lo[e] : hi[e];
+      acc_e[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fe, __builtin_bit_cast(bf16x8, bs), acc_e[j], 0, 0, 0);
+    }
+  };
+
+  // One slab.  Upper half: its 16 MFMAs (column block by column block), the reads of the lower row
+  // blocks behind the first two; the last column block, whose reads were issued last in the slab
+  // before, is waited for in front of its first MFMA.  Then the slab's one barrier (as in mfma_tile:
+  // slot kt is consumed, slab kt+1 has landed).  Lower half: its 16 MFMAs; behind them the reads of
+  // slab kt+1 -- upper row blocks and edge block first, each column block as soon as its four MFMAs
+  // are issued -- and the loads of slab kt+NS.
+  auto do_slab = [&](int kt, auto kmc, auto edgec) {
+    constexpr int KM = decltype(kmc)::value;
+    constexpr bool FAST = KM >= 0, EDGE = decltype(edgec)::value;
+    const bool fetch = FAST || kt + C::NS < nk;
+    const bool more = FAST || kt + 1 < nk;
+    const int st = kt % C::NS, st_next = (kt + 1) % C::NS;
+    constexpr int ST_FETCH = FAST ? KM : -1;
+    constexpr int ST_NEXT = FAST ? (KM + 1) % C::NS : 0;
+    static_for<16>([&](auto ic) {
+      constexpr int i = decltype(ic)::value, b = i / 4, a = (b & 1) ? 3 - i % 4 : i % 4;
+      if constexpr (i == 12) WAIT2_BEFORE8(hb);   // (nothing to wait for in slab 0: the prologue waited for everything)
+      __builtin_amdgcn_sched_barrier(0);
+      acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag(ha0, 2 * a), frag(hb, 2 * b), acc[a][b], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (i < 2) {
+        static_for<4>([&](auto jc) {
+          constexpr int u = 4 * i + decltype(jc)::value;
+          if constexpr (FAST) read_a_at(ha1, IntC<1>{}, IntC<(KM >= 0 ? KM : 0)>{}, IntC<u>{});
+          else read_a(ha1, IntC<1>{}, st, IntC<u>{});
+        });
+      }
+    });
+    if constexpr (EDGE) edge_mma();
+    __builtin_amdgcn_sched_barrier(0);
+    WAIT8(ha1);
+    if constexpr (!FAST) mask_units(ha1, kt);
+    if (FAST || kt + C::NS - 1 < nk) {
+      if (EDGE && wave == 0) wait_vmcnt<(C::NS - 2) * (C::L + 1)>(); else wait_vmcnt<(C::NS - 2) * C::L>();
+    } else {
+      wait_vmcnt<0>();
+    }
+    __builtin_amdgcn_s_barrier();
+    static_for<16>([&](auto ic) {
+      constexpr int i = decltype(ic)::value, b = i / 4, a = (b & 1) ? 3 - i % 4 : i % 4;
+      __builtin_amdgcn_sched_barrier(0);
+      acc[4 + a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag(ha1, 2 * a), frag(hb, 2 * b), acc[4 + a][b], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (i < 2) {
+        static_for<4>([&](auto jc) {
+          constexpr int u = 4 * i + decltype(jc)::value;
+          if constexpr (FAST) read_a_at(ha0, IntC<0>{}, IntC<ST_NEXT>{}, IntC<u>{});
+          else if (more) read_a(ha0, IntC<0>{}, st_next, IntC<u>{});
+        });
+      }
+      if constexpr (EDGE && i == 2) {
+        if constexpr (FAST) read_e_at(IntC<ST_NEXT>{});
+        else if (more) read_e(st_next);
+      }
+      if constexpr (i % 4 == 3) {                  // column block b has had its last MFMA of this slab
+        static_for<2>([&](auto jc) {
+          constexpr int u = 2 * b + decltype(jc)::value;
+          if constexpr (FAST) read_b_at(IntC<ST_NEXT>{}, IntC<u>{});
+          else if (more) read_b(st_next, IntC<u>{});
+        });
+      }
+      // loads of slab kt+NS: one behind each of MFMAs 4, 5, 6, 8, 9, 10
+      static_for<C::L>([&](auto lc) {
+        constexpr int l = decltype(lc)::value;
+        if constexpr ((l < 3 ? 4 + l : 5 + l) == i) {
+          if constexpr (FAST) issue_one(lc, IntC<ST_FETCH>{});
+          else if (fetch) issue_one(lc, IntC<-1>{});
+        }
+      });
+      if constexpr (EDGE && i == 12) {
+        if (fetch && wave == 0) issue_edge(IntC<ST_FETCH>{});
+      }
+    });
+    if (fetch) next_slab();
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) {
+      WAIT8_6_2_BUT2(ha0, hb, he);
+      if constexpr (!FAST) {
+        mask_units(ha0, kt + 1);
+        if constexpr (EDGE) mask_edge(kt + 1);
+      }
+    }
+  };
+
+  // Steady state: slabs whose fetch (of slab kt + NS) exists and is complete, in groups of NS so that
+  // the ring slot is a compile-time constant.
+  const bool last_ragged = (klen % C::BK) != 0;
+  const int n_fast_raw = (nk - C::NS - (last_ragged ? 1 : 0)) / C::NS * C::NS;
+  const int n_fast = n_fast_raw > 0 ? n_fast_raw : 0;
+  auto run_slabs = [&](auto edgec) {
+    int kt = 0;
+    for (; kt < n_fast; kt += C::NS)
+      static_for<C::NS>([&](auto kmc) { do_slab(kt + decltype(kmc)::value, kmc, edgec); });
+    for (; kt < nk; ++kt) do_slab(kt, IntC<-1>{}, edgec);
+  };
+  if (has_edge) run_slabs(IntC<1>{}); else run_slabs(IntC<0>{});
+  TIMELINE_STAMP(q, item, 2);
+
+  // accumulator register v of a 16 x 16 block: row (lane / 16) * 4 + v, column lane % 16
+  auto stage_half = [&](int h, float* dst) {
+    static_for<4 * C::TN>([&](auto blk_c) {
+      constexpr int a = decltype(blk_c)::value / C::TN, b = decltype(blk_c)::value % C::TN;
+      float* base = dst + (a * 16 + (lane >> 4) * 4) * C::EPI_PITCH + b * 16 + (lane & 15);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) base[v * C::EPI_PITCH] = h == 0 ? acc[a][b][v] : acc[4 + a][b][v];
+    });
+  };
+  auto emit_edge = [&](int64_t E) {
+    if (!has_edge) return;
+    // edge block rows 0-7 are the leading group, 8-15 the group of the trailing row
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int64_t col = col0 + wn0 + (2 * edge_blk + j) * 16 + (lane & 15);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int r = (lane >> 4) * 4 + v;
+        int64_t row;
+        if (r < 8) row = q.lead_base >= 0 ? q.lead_base + r : -1;
+        else row = (q.trail_row >= 0 && (q.trail_row & 7) == r - 8) ? q.trail_row : -1;
+        const int64_t flat = row * p.in + col;
+        if (row >= 0 && col < p.in && flat >= p.begin && flat < p.end)
+          emit<MODE>(q.s, E, slab, flat - p.begin, flat, acc_e[j][v]);
+      }
+    }
+  };
+  tile_epilogue<C, MODE>(q, ldsb, row0, col0, slab, wave, lane, tid, stage_half, emit_edge);
   TIMELINE_STAMP(q, item, 3);
 }
 
@@ -954,7 +1377,8 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_mfma_kernel(const MfmaArgs arg
     if (j < 32 && (j & 1))
       for (int i = 0; i < q.stagger; ++i) __builtin_amdgcn_s_sleep(127);
   }
-  mfma_tile<C, MODE>(q, item, ldsb);
+  if constexpr (C::MI == 16) mfma_tile16<C, MODE>(q, item, ldsb);
+  else mfma_tile<C, MODE>(q, item, ldsb);
 }
 
 // ---------------------------------------------------------------------------
@@ -1014,6 +1438,7 @@ __global__ __launch_bounds__(C::NT, 2) void wgrad_group_kernel(const GroupParams
   const MfmaParams& q = gp.seg[si];
   const int local = item - gp.item_start[si];
   if (q.tiles_m == 0) colsum_item<C, EMIT_ADAMW>(q, local, ldsb);
+  else if constexpr (C::MI == 16) mfma_tile16<C, EMIT_ADAMW>(q, local, ldsb);
   else mfma_tile<C, EMIT_ADAMW>(q, local, ldsb);
 }
 
@@ -1470,8 +1895,15 @@ constexpr int kStaggerAdamW = 6;
 // late, so that the epilogues of half the part fall into the loops of the other half (measured at
 // T = 8192: 1 - 3 % at 10, nothing from 24 on).
 constexpr int kStaggerAdamWLarge = 10;
-using MainCfg = RingCfg<2, 4>;    // 256 x 256 tiles, four slabs of 33 KB in LDS, one workgroup per compute unit
-using FusedCfg = RingCfg<1, 3>;   // 128 x 256 tiles, three slabs of 25 KB, two workgroups per compute unit
+// 256 x 256 tiles, four slabs of 33 KB in LDS, one workgroup per compute unit: both waves of a SIMD are in
+// the loop together, which the 16x16x32 MFMA needs (a wave then issues one MFMA per 32 cycles; alone
+// on its SIMD it would have to issue one per 16 cycles beside its reads and loads, and cannot)
+using MainCfg = RingCfg<2, 4, 16>;
+// 128 x 256 tiles, three slabs of 25 KB, two workgroups per compute unit: while its partner is in its
+// epilogue a workgroup's waves are alone on their SIMDs, so this one keeps the 32x32x16 MFMA (with the
+// other shape its loops were 10 % slower).  The two shapes give the same bits: the hardware adds the
+// tokens of either in the same order.
+using FusedCfg = RingCfg<1, 3, 32>;
                                   // (the fused call, and plain gradients with few tiles)
 
 template <class C, int MODE>
@@ -1589,17 +2021,13 @@ int launch_wgrad_bf16_mfma(const WgradProblem& p, int mode, const Sinks& s, void
     if (fused_takes_large_tile(p)) return launch_mfma_cfg<MainCfg>(p, mode, s, (hipStream_t)stream);
     return launch_mfma_cfg<FusedCfg>(p, mode, s, (hipStream_t)stream);
   }
-  // A segment whose large tiles would occupy at most half the compute units takes the small
-  // tile too: twice the workgroups, each element still summed over the tokens in the same order.
-  // So does a call with few tokens per slab: its loops are short, and two workgroups per compute unit,
-  // which drift apart, spread the bursts of stores that one workgroup per compute unit sends out in
-  // step (measured on 32 Mi elements of 14336 x 4096: 77 - 81 against 79 - 84 us at 1024 tokens, 122 - 128
-  // against 123 - 133 us at 2048, on 4096 x 14336 88 against 100 us; from 4096 tokens on the large tile's
-  // third less operand traffic wins, 212 against 220 us).
+  // The plain gradient takes whichever tile is faster for its number of tiles and tokens
+  // (plain_takes_large_tile, csrc/shape.cpp); every element is summed over the tokens in the same
+  // order either way.
   const RowSplit rs = split_rows(p);
   const int64_t big_tiles = ceil_div(rs.rb1 - rs.rb0, MainCfg::BM) * ceil_div(p.in, MainCfg::BN) * p.S;
   const int64_t slab_tokens = p.S > 1 ? p.kslab : p.T;
-  if (big_tiles <= device_compute_units() / 2 || slab_tokens <= 2048)
+  if (!plain_takes_large_tile(big_tiles, slab_tokens, device_compute_units()))
     return launch_mfma_cfg<FusedCfg>(p, mode, s, (hipStream_t)stream);
   return launch_mfma_cfg<MainCfg>(p, mode, s, (hipStream_t)stream);
 }

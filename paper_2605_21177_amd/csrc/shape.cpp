@@ -63,6 +63,28 @@ bool fused_takes_large_tile(const WgradProblem& p) {
   return p.T >= 6144 && p.in >= ((int64_t(128) << 20) / 2 + p.T - 1) / p.T;
 }
 
+// Which tile the plain gradient takes.  The 256 x 256 tile (one workgroup per compute unit) runs its
+// rounds faster the more tokens a slab has -- measured ratio of a full round against the 128 x 256
+// tile's (two workgroups per unit): 1.05 at 768 tokens, 0.99 at 1024, 0.95 at 1536, 0.91 at 2048,
+// 0.88 at 3072, 0.85 at 8192, fitted by 0.83 + 160 / T -- but pays for a partly filled last round in
+// whole tiles where the small tile pays in half ones.  With w = tiles / compute units, a partly
+// filled round costs about 0.6 + 0.4 x (its fill) of a full one (the units that work alone run
+// faster): cost(w) = floor(w) + (0.6 + 0.4 frac(w) if frac(w) > 0), and the small tile's cost in the
+// same unit is cost(2 w) / 2.  On 75 measured cases (12 shapes, 768 - 8192 tokens) the rule below is
+// within 0.3 % of the better tile on average and never more than 4 % off; "small tile up to 2048
+// tokens" was 2.5 % off on average and up to 15 %.
+bool plain_takes_large_tile(int64_t large_tiles, int64_t slab_tokens, int compute_units) {
+  const double cus = compute_units > 0 ? compute_units : kDefaultComputeUnits;
+  if (large_tiles <= (int64_t)(cus / 2)) return false;          // too few tiles to fill the device: twice as many small ones
+  const auto cost = [](double w) {
+    const double fl = (double)(int64_t)w, fr = w - fl;
+    return fl + (fr > 1e-9 ? 0.6 + 0.4 * fr : 0.0);
+  };
+  const double w = (double)large_tiles / cus;
+  const double round_ratio = 0.83 + 160.0 / (double)(slab_tokens > 0 ? slab_tokens : 1);
+  return round_ratio * cost(w) / (cost(2.0 * w) / 2.0) < 0.99;
+}
+
 Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T, int64_t begin,
                  int64_t end, int32_t forced, bool mfma, int compute_units) {
   (void)out; (void)dtype;

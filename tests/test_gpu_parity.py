@@ -201,9 +201,11 @@ def test_bf16_ranges_with_chunk_arrays_at_the_tensor_phase(begin, end):
 
 @pytest.mark.parametrize("T", [70, 96, 161, 2070, 2080])
 def test_bf16_many_tiles_at_short_and_long_token_counts(T):
-    """More than 128 tiles of 256 x 256 and a range with edge rows.  Up to 2048 tokens the plain gradient
-    runs on the small tile (two workgroups per compute unit), beyond on the large one; token counts
-    that leave a ragged last slab (70, 161, 2070) or none (96, 2080)."""
+    """More than 128 tiles of 256 x 256 and a range with edge rows.  At the short token counts the plain
+    gradient runs on the small tile (two workgroups per compute unit, 32x32x16 MFMAs), at the long ones on
+    the large one (16x16x32 MFMAs) while the fused call stays on the small tile: the bit-identity of
+    fused and un-fused results then holds across the two tiles and MFMA shapes.  Token counts that leave
+    a ragged last slab (70, 161, 2070) or none (96, 2080)."""
     rng = np.random.default_rng([83, T])
     case = WL.linear_case(rng, "many tiles", 2400, 4096, T, WL.BF16, 1e-3)
     _full_check(case, 4096 * 3 + 77, 4096 * 2397 + 5, check_accum=True)
