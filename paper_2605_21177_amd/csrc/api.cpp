@@ -293,7 +293,7 @@ GroupPlan plan_group(const chunkft_group_segment* segs, int32_t n) {
     g.grouped[static_cast<size_t>(i)] = take ? 1 : 0;
     if (take && !vec) {
       any = true;
-      all_large = all_large && fused_takes_large_tile(c.p);
+      all_large = all_large && fused_takes_large_tile(c.p, cus);
     }
     if (!take) {
       const size_t need = workspace_need(&sg.layer, c.p);

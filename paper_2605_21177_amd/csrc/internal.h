@@ -82,7 +82,7 @@ Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T
 // The fused call takes the 256 x 256 tile (one workgroup per compute unit) instead of the 128 x 256
 // one (two per compute unit) when it is compute-bound and its operands are too large to stay in
 // the last-level cache (shape.cpp).
-bool fused_takes_large_tile(const WgradProblem& p);
+bool fused_takes_large_tile(const WgradProblem& p, int compute_units);
 
 // One segment of a grouped fused call: a bf16 matrix segment for the MFMA kernel (S = 1) or a
 // bf16 scale-vector segment whose normalised input the caller supplies.

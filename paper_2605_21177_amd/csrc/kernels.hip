@@ -2018,7 +2018,7 @@ int launch_wgrad_bf16_mfma(const WgradProblem& p, int mode, const Sinks& s, void
   // The plain gradient (short epilogue) is a little faster on the large tile; the fused call,
   // whose epilogue moves 26 bytes per element, gains from two workgroups per compute unit.
   if (mode == EMIT_ADAMW) {
-    if (fused_takes_large_tile(p)) return launch_mfma_cfg<MainCfg>(p, mode, s, (hipStream_t)stream);
+    if (fused_takes_large_tile(p, device_compute_units())) return launch_mfma_cfg<MainCfg>(p, mode, s, (hipStream_t)stream);
     return launch_mfma_cfg<FusedCfg>(p, mode, s, (hipStream_t)stream);
   }
   // The plain gradient takes whichever tile is faster for its number of tiles and tokens

@@ -10,6 +10,11 @@ namespace chunkft {
 
 namespace {
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+// rounds of work for w tiles per compute unit: a partly filled round costs 0.6 + 0.4 x its fill
+inline double round_cost(double w) {
+  const double fl = (double)(int64_t)w, fr = w - fl;
+  return fl + (fr > 1e-9 ? 0.6 + 0.4 * fr : 0.0);
+}
 }  // namespace
 
 // Body = complete rows from the first multiple of 8 on.  Everything before it
@@ -53,16 +58,6 @@ bool mfma_path_ok(const WgradProblem& p) {
   return true;
 }
 
-// Long token counts make the fused call compute-bound (2 T flops against 26 bytes per element: from
-// about 4000 tokens on), and when the operands are also too large to stay in the last-level
-// cache the large tile's third less operand traffic decides: measured at T = 8192 on the
-// 70B-shaped MLP (X of 128 and 448 MiB) 1.03 against 1.14 ms and 1.25 against 1.37 ms for a
-// 128 MiB chunk, 3.46 against 4.07 ms for the whole gate projection; with X of 64 MiB
-// (in = 4096) the two tiles are level at T = 8192 and the small one wins below.
-bool fused_takes_large_tile(const WgradProblem& p) {
-  return p.T >= 6144 && p.in >= ((int64_t(128) << 20) / 2 + p.T - 1) / p.T;
-}
-
 // Which tile the plain gradient takes.  The 256 x 256 tile (one workgroup per compute unit) runs its
 // rounds faster the more tokens a slab has -- measured ratio of a full round against the 128 x 256
 // tile's (two workgroups per unit): 1.05 at 768 tokens, 0.99 at 1024, 0.95 at 1536, 0.91 at 2048,
@@ -76,13 +71,27 @@ bool fused_takes_large_tile(const WgradProblem& p) {
 bool plain_takes_large_tile(int64_t large_tiles, int64_t slab_tokens, int compute_units) {
   const double cus = compute_units > 0 ? compute_units : kDefaultComputeUnits;
   if (large_tiles <= (int64_t)(cus / 2)) return false;          // too few tiles to fill the device: twice as many small ones
-  const auto cost = [](double w) {
-    const double fl = (double)(int64_t)w, fr = w - fl;
-    return fl + (fr > 1e-9 ? 0.6 + 0.4 * fr : 0.0);
-  };
   const double w = (double)large_tiles / cus;
   const double round_ratio = 0.83 + 160.0 / (double)(slab_tokens > 0 ? slab_tokens : 1);
-  return round_ratio * cost(w) / (cost(2.0 * w) / 2.0) < 0.99;
+  return round_ratio * round_cost(w) / (round_cost(2.0 * w) / 2.0) < 0.99;
+}
+
+// Which tile the fused call takes.  Its AdamW epilogue is HBM-bound and overlaps the partner's loop
+// only on the small tile, so the large tile pays only when the loops dominate: measured ratio of the
+// large tile's time to the small one's on fully filled rounds 1.05 - 1.10 at 3072 - 4096 tokens, 0.98 -
+// 0.99 (in = 4096) and 0.89 (in = 8192) at 6144, 0.84 - 0.93 at 8192, fitted by 0.55 + 2600 / T; partly
+// filled rounds are priced as for the plain gradient.  The rule agrees with the faster tile in all 16
+// measured cases (four shapes x 3072 - 8192 tokens; X from 24 to 224 MiB).
+bool fused_takes_large_tile(const WgradProblem& p, int compute_units) {
+  const double cus = compute_units > 0 ? compute_units : kDefaultComputeUnits;
+  const RowSplit rs = split_rows(p);
+  const int64_t rows = rs.rb1 > rs.rb0 ? rs.rb1 - rs.rb0 : 0;
+  const int64_t tiles = ceil_div(rows, kMainTileM) * ceil_div(p.in, kMainTileN) * (p.S > 0 ? p.S : 1);
+  if (tiles <= (int64_t)(cus / 2)) return false;
+  const int64_t slab_tokens = p.S > 1 ? p.kslab : p.T;
+  const double w = (double)tiles / cus;
+  const double round_ratio = 0.55 + 2600.0 / (double)(slab_tokens > 0 ? slab_tokens : 1);
+  return round_ratio * round_cost(w) / (round_cost(2.0 * w) / 2.0) < 0.99;
 }
 
 Split pick_split(int32_t kind, int32_t dtype, int64_t out, int64_t in, int64_t T, int64_t begin,
