@@ -336,8 +336,10 @@ def main():
                          "frac_of_random_operand_rate": round(wgrad_tflops / ceil_rand[0], 4),
                          "random_operands_16x16x32": {"tflops": round(ceil_rand16[0], 1),
                                                       "shader_mhz": round(ceil_rand16[1]),
+                                                      "frac_of_this_rate": round(wgrad_tflops / ceil_rand16[0], 4),
                                                       "what": "the other bf16 shape draws less power and holds "
-                                                              "a higher clock when nothing else runs beside it"}}},
+                                                              "a higher clock; the gradient kernel's 256 x 256 "
+                                                              "tile, which this workload takes, issues it"}}},
         "roofline_adamw": {"kernel": "elementwise_kernel (chunkft_adamw_chunk)", "bound": "hbm",
                            "achieved": round(adamw_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                            "frac": round(adamw_gbps / PEAK_HBM_GBPS, 4), "traffic": MEASURED_TRAFFIC["adamw"],

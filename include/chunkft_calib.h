@@ -44,8 +44,9 @@ int chunkft_calib_mfma_bf16(int32_t random_operands, int32_t steps, void* scratc
 
 /* The same measurement for either bf16 MFMA shape.
  *   shape  32: 32x32x16 (what the call above runs, and what the weight-gradient kernel
- *              issues); 16: 16x16x32, sixteen per step on 4 x 4 accumulator blocks, the
- *              same flop count per step.  Anything else: CHUNKFT_ERR_INVALID_ARG.
+ *              issues on its 128 x 256 tile); 16: 16x16x32 (what it issues on its 256 x 256
+ *              tile), sixteen per step on 4 x 4 accumulator blocks, the same flop count per
+ *              step.  Anything else: CHUNKFT_ERR_INVALID_ARG.
  * The two shapes do the same work per cycle but do not draw the same power, so under
  * the clock limit their sustained rates differ. */
 int chunkft_calib_mfma_bf16_shape(int32_t shape, int32_t random_operands, int32_t steps, void* scratch,
